@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Bench of the RMM linear layer (Algorithm 1 forward + backward) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--kind gaussian|rademacher]
+
+A step is one forward + one backward of a single layer on a synthetic batch that
+is already resident in HBM.  The default workload is the headline shape
+(N = 4096 tokens, 768 -> 3072, bf16, k = 410 = 10 % of N, Gaussian sketch).
+Prints ONE JSON line: whole-step throughput in TFLOP/s of the flops Algorithm 1
+executes, the roofline of the slowest stage (timed with HIP events inside the
+timed region), and the fp64 oracle timed on the host cores as a plain baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3       # MI355X fp32 vector
+PEAK_HBM_GBS = 8000.0
+
+STAGES = ["fwd_Y", "fwd_Xproj", "bwd_dX", "bwd_G", "bwd_dW"]
+
+
+def stage_flops(n, d_in, d_out, k):
+    return {"fwd_Y": 2 * n * d_in * d_out, "fwd_Xproj": 2 * n * k * d_in, "bwd_dX": 2 * n * d_in * d_out,
+            "bwd_G": 2 * n * k * d_out, "bwd_dW": 2 * k * d_in * d_out}
+
+
+def stage_bytes(n, d_in, d_out, k, e):
+    """Algorithmic HBM bytes of each stage: every operand read once, every result written once, none for S."""
+    return {"fwd_Y": e * (n * d_in + d_in * d_out + n * d_out), "fwd_Xproj": e * (n * d_in + k * d_in),
+            "bwd_dX": e * (n * d_out + d_in * d_out + n * d_in), "bwd_G": e * (n * d_out + k * d_out),
+            "bwd_dW": e * (k * d_out + k * d_in + d_in * d_out)}
+
+
+def read_traffic(workload, stage):
+    """HBM bytes per launch of `stage` from the committed counter summary, if any
+    (line `traffic_bytes_per_launch <workload> <stage> <bytes>` in profiles/hbm_traffic.txt)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        t = line.split()
+        if len(t) == 4 and t[0] == "traffic_bytes_per_launch" and t[1] == workload and t[2] == stage:
+            return float(t[3])
+    return None
+
+
+def cpu_baseline(cfg, kind, budget_s=10.0):
+    """fp64 oracle forward + backward of the same layer on the host cores."""
+    import numpy as np
+    from oracle import rmm as o_rmm
+    from paper_2201_13195_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    X, W, dY = synth.layer_inputs(cfg["n"], cfg["d_in"], cfg["d_out"], cfg["dtype"], cfg["seeds"])
+    X, W, dY = synth.to_f64(X), synth.to_f64(W), synth.to_f64(dY)
+    fl = sum(stage_flops(cfg["n"], cfg["d_in"], cfg["d_out"], cfg["k"]).values())
+
+    def step():
+        _, Xp = o_rmm.forward(X, W, None, cfg["k"], kind, cfg["seed"], 0)
+        o_rmm.backward(dY, W, Xp, kind, cfg["seed"], 0)
+
+    step()
+    t0 = time.perf_counter()
+    reps = 0
+    while True:
+        step()
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt >= budget_s or reps >= 20:
+            break
+    return {"value": fl * reps / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": "%d full forward+backward step(s) of the same workload in fp64 numpy, %.1f s" % (reps, dt),
+            "ms_per_step": dt / reps * 1e3}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c3_base_ffn_up")
+    ap.add_argument("--kind", default="gaussian", choices=["gaussian", "rademacher"])
+    ap.add_argument("--k", type=int, default=0, help="override the sketch size")
+    ap.add_argument("--sets", type=int, default=4, help="rotating input/output sets (keeps the working set above the 256 MB last-level cache)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 (no collective or sharded path exists)",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2201_13195_amd as rmm
+    from paper_2201_13195_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    cfg = dict(synth.CONFIGS[args.workload])
+    if args.k:
+        cfg["k"] = args.k
+    kind = rmm.GAUSSIAN if args.kind == "gaussian" else rmm.RADEMACHER
+    n, d_in, d_out, k = cfg["n"], cfg["d_in"], cfg["d_out"], cfg["k"]
+    tdtype = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
+    esize = 2 if cfg["dtype"] == "bf16" else 4
+
+    Xc, Wc, dYc = synth.layer_inputs(n, d_in, d_out, cfg["dtype"], cfg["seeds"])
+    sets = []
+    for s in range(max(1, args.sets)):
+        # every set holds the same values (so results are comparable) at its own addresses
+        sets.append(dict(X=Xc.to(dev).clone(), W=Wc.to(dev).clone(), dY=dYc.to(dev).clone(),
+                         Y=torch.empty((n, d_out), dtype=tdtype, device=dev),
+                         Xp=torch.empty((k, d_in), dtype=tdtype, device=dev),
+                         dX=torch.empty((n, d_in), dtype=tdtype, device=dev),
+                         dW=torch.empty((d_out, d_in), dtype=tdtype, device=dev)))
+    ws_bytes = max(rmm.rmm_workspace_bytes(n, d_in, d_out, k, tdtype, kind, binding.OP_FORWARD),
+                   rmm.rmm_workspace_bytes(n, d_in, d_out, k, tdtype, kind, binding.OP_BACKWARD), 16)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    seed = cfg["seed"]
+
+    def step(i, profile=None):
+        b = sets[i % len(sets)]
+        pf = profile if profile is not None and profile[0] < 2 else None
+        pb = profile if profile is not None and profile[0] >= 2 else None
+        rmm.rmm_forward(b["X"], b["W"], None, k, kind, seed, i, Y=b["Y"], X_proj=b["Xp"], ws=ws, profile=pf)
+        rmm.rmm_backward(b["dY"], b["W"], b["Xp"], kind, seed, i, dX=b["dX"], dW=b["dW"], ws=ws, profile=pb)
+
+    def new_events(count):
+        evs = []
+        for _ in range(count):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            b.record()          # recording once creates the handles the library re-records
+            evs.append((a, b))
+        torch.cuda.synchronize()
+        return evs
+
+    # ---- warm-up; the last warm-up steps also time every stage once to find the slowest
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    stage_ms = {}
+    reps = 5
+    for sidx, name in enumerate(STAGES):
+        evs = new_events(reps)
+        for r in range(reps):
+            step(r, (sidx, evs[r][0], evs[r][1]))
+        torch.cuda.synchronize()
+        stage_ms[name] = sorted(a.elapsed_time(b) for a, b in evs)[reps // 2]
+    dominant = max(stage_ms, key=stage_ms.get)
+    dom_idx = STAGES.index(dominant)
+
+    # ---- timed region: exactly `steps` steps, events around the dominant stage of every step
+    evs = new_events(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, (dom_idx, evs[i][0], evs[i][1]))
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    dom_ms = sum(a.elapsed_time(b) for a, b in evs) / args.steps
+
+    fl = stage_flops(n, d_in, d_out, k)
+    by = stage_bytes(n, d_in, d_out, k, esize)
+    total_flops = sum(fl.values())
+    ms_per_step = dt / args.steps * 1e3
+    value = total_flops / (ms_per_step * 1e-3) / 1e12
+    peak = PEAK_BF16_TFLOPS if cfg["dtype"] == "bf16" else PEAK_F32_TFLOPS
+    achieved = fl[dominant] / (dom_ms * 1e-3) / 1e12
+    saved = k * d_in * esize + 16
+    out = {
+        "metric": "RMM layer fwd+bwd TFLOP/s (executed flops of Algorithm 1) at N=%d, %d->%d" % (n, d_in, d_out),
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": "%s: N=%d tokens, d_in=%d, d_out=%d, k=%d (%s sketch), %s, X,dY~N(0,1), "
+                               "W~N(0,0.02^2), %d rotating buffer sets"
+                               % (args.workload, n, d_in, d_out, k, args.kind, cfg["dtype"], len(sets)),
+                   "flops_per_step": total_flops,
+                   "saved_activation_bytes": saved, "plain_layer_saved_bytes": n * d_in * esize,
+                   "saved_fraction": saved / (n * d_in * esize)},
+        "roofline": {"bound": "mfma", "kernel": dominant, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": read_traffic(args.workload, dominant),
+                     "avg_launch_ms": dom_ms, "flops_per_launch": fl[dominant],
+                     "algorithmic_bytes_per_launch": by[dominant]},
+        "stages_ms": stage_ms,
+        "stages_tflops": {s: fl[s] / (stage_ms[s] * 1e-3) / 1e12 for s in STAGES},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, kind)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

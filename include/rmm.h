@@ -1,0 +1,154 @@
+/*
+ * rmm.h -- C ABI of the randomized-matrix-multiplication (RMM) linear layer for
+ * AMD MI355X (gfx950).
+ *
+ * The layer is the one of "Memory-Efficient Backpropagation through Large Linear
+ * Layers" (arXiv 2201.13195), Section 2.1 and Algorithm 1: the forward pass
+ * returns Y = X W^T (+ 1 b^T) and keeps only X_proj = S^T X (k x d_in) plus a
+ * 16-byte PRNG state instead of X (N x d_in); the backward pass returns the exact
+ * dX = dY W and the unbiased estimate dW = (S^T dY)^T X_proj, with the N x k
+ * sketch S re-made from the state (it never exists in memory).
+ *
+ * Conventions shared by every entry point
+ *   - Matrix arguments are DEVICE pointers to dense, row-major, contiguous
+ *     arrays whose base address is 16-byte aligned.  The caller allocates and
+ *     owns all of them; the library never allocates, frees or keeps a pointer.
+ *   - `ws` is caller-provided device scratch of at least
+ *     rmm_workspace_bytes(...) bytes (16-byte aligned); its contents are
+ *     undefined on entry and on return.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
+ *     work is enqueued on it and the call returns without waiting.
+ *   - Output buffers are overwritten, never accumulated into.
+ *   - Return value: RMM_OK or a negative rmm_status_t.  Nothing is printed, no
+ *     exception crosses the boundary, the process is never aborted.  On an
+ *     error return no kernel has been launched.
+ *   - The library holds no mutable global state; calls are re-entrant.
+ *   - dtype RMM_DTYPE_BF16: inputs, Y, dX, X_proj, dW are bfloat16 (round to
+ *     nearest even from fp32 accumulators); bias / dbias are bfloat16 too.
+ *     dtype RMM_DTYPE_F32: everything is fp32.
+ *
+ * The sketch.  state = (seed, offset).  Entry (i, j) of S (token i, sketch
+ * column j) is P[i][j] / sqrt(k), with P a pure function of (state, i, j) built
+ * on Philox-4x32-10 with key (seed mod 2^32, seed div 2^32):
+ *   Gaussian   (Eq. 5): call counter (i div 8, j, offset mod 2^32, offset div 2^32)
+ *              gives words r0..r3; w = r[(i mod 8) div 2];
+ *              u1 = ((w div 2^16) + 1/2) / 2^16, u2 = (w mod 2^16) / 2^16;
+ *              P = sqrt(-2 ln u1) * (cos(2 pi u2) if i even, sin(2 pi u2) if i odd).
+ *   Rademacher (Section 3.4): call counter (i div 128, j, offset lo, offset hi);
+ *              t = i mod 128; bit = (r[t div 32] >> (t mod 32)) & 1; P = 1 - 2 bit.
+ * Entries do not depend on n or k, so a forward and a backward call that pass
+ * the same state, k and kind see the same S (Algorithm 1, "rematerialize S").
+ * The caller must use a fresh offset for every forward call so that sketches of
+ * different layers and steps are independent of each other and of dY
+ * (Section 2.1, the independence requirement below Eq. 4).
+ */
+#ifndef RMM_H_
+#define RMM_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RMM_OK = 0,
+    RMM_ERR_INVALID_ARG = -1, /* NULL required pointer, non-positive size, unknown enum, misaligned pointer */
+    RMM_ERR_UNSUPPORTED = -2, /* sizes beyond the documented limits */
+    RMM_ERR_WORKSPACE = -3,   /* ws is NULL or ws_bytes is below rmm_workspace_bytes() */
+    RMM_ERR_LAUNCH = -4       /* the HIP runtime refused a launch */
+} rmm_status_t;
+
+typedef enum { RMM_DTYPE_F32 = 0, RMM_DTYPE_BF16 = 1 } rmm_dtype_t;
+typedef enum { RMM_SKETCH_GAUSSIAN = 0, RMM_SKETCH_RADEMACHER = 1 } rmm_sketch_kind_t;
+typedef enum { RMM_OP_FORWARD = 0, RMM_OP_BACKWARD = 1, RMM_OP_SKETCH = 2 } rmm_op_t;
+
+/* The "PRNG state" saved between forward and backward (Algorithm 1): 16 bytes. */
+typedef struct {
+    uint64_t seed;
+    uint64_t offset;
+} rmm_rng_state_t;
+
+/* Shape of one layer call.  n = tokens (rows of X; the paper's B), k = sketch
+ * size (the paper's B_proj).  Limits: 1 <= n, d_in, d_out, k < 2^31 and every
+ * matrix below 2^40 elements; k > n is accepted (Section 2.1 only asks for
+ * E[S S^T] = I). */
+typedef struct {
+    int64_t n, d_in, d_out, k;
+    int32_t dtype; /* rmm_dtype_t */
+    int32_t kind;  /* rmm_sketch_kind_t */
+} rmm_layer_desc_t;
+
+/* Scratch bytes the given operation needs for this shape.  For RMM_OP_SKETCH
+ * only n, k, dtype, kind and d_in (= the operand's column count d) are read.
+ * Returns 0 for an invalid descriptor. */
+size_t rmm_workspace_bytes(const rmm_layer_desc_t *desc, int op);
+
+/* Static, NUL-terminated description of a status code. */
+const char *rmm_status_string(int status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int rmm_version(void);
+
+/* Randomized-matmul primitive (Eq. 4, second line): A_proj[k x d] = S^T A[n x d].
+ * A: device, read only.  A_proj: device, written.  Output dtype = dtype. */
+int rmm_sketch(int64_t n, int64_t d, int64_t k, int dtype, int kind, rmm_rng_state_t state,
+               const void *A, void *A_proj, void *ws, size_t ws_bytes, void *stream);
+
+/* Algorithm 1, Forward: Y[n x d_out] = X[n x d_in] W[d_out x d_in]^T (+ bias[d_out] on
+ * every row if bias != NULL; Eq. 1), X_proj[k x d_in] = S^T X.  After the call the
+ * caller may drop X and keeps X_proj and `state` for the backward call: the saved
+ * bytes are k*d_in*sizeof(dtype) + 16 instead of n*d_in*sizeof(dtype) (Section 2.4.1). */
+int rmm_forward(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *X, const void *W,
+                const void *bias, void *Y, void *X_proj, void *ws, size_t ws_bytes, void *stream);
+
+/* Algorithm 1, Backward, with the state given to the forward call:
+ * dX[n x d_in] = dY[n x d_out] W (Eq. 2), dW[d_out x d_in] = (S^T dY)^T X_proj,
+ * and, if dbias != NULL, dbias[d_out] = dY^T 1 (Eq. 3).  dX may be NULL to skip
+ * the input gradient (first layer of a network). */
+int rmm_backward(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *dY, const void *W,
+                 const void *X_proj, void *dX, void *dW, void *dbias, void *ws, size_t ws_bytes,
+                 void *stream);
+
+/* Stages of the two passes, for the profiled variants below. */
+typedef enum {
+    RMM_STAGE_NONE = -1,
+    RMM_STAGE_FWD_Y = 0,      /* Y = X W^T (+ bias)          */
+    RMM_STAGE_FWD_XPROJ = 1,  /* X_proj = S^T X              */
+    RMM_STAGE_BWD_DX = 2,     /* dX = dY W                   */
+    RMM_STAGE_BWD_G = 3,      /* G = S^T dY (into workspace) */
+    RMM_STAGE_BWD_DW = 4,     /* dW = G^T X_proj             */
+    RMM_STAGE_BWD_DBIAS = 5   /* dbias = dY^T 1              */
+} rmm_stage_t;
+
+/* Measurement hooks: identical to rmm_forward / rmm_backward, and in addition
+ * record the hipEvent_t `ev_begin` on `stream` right before the kernels of
+ * `stage` and `ev_end` right after them, so a caller can time one stage inside
+ * a full pass.  Events are created and owned by the caller.  A stage that does
+ * not run in this call (wrong pass, dX or dbias skipped) records nothing. */
+int rmm_forward_profiled(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *X, const void *W,
+                         const void *bias, void *Y, void *X_proj, void *ws, size_t ws_bytes, void *stream,
+                         int stage, void *ev_begin, void *ev_end);
+int rmm_backward_profiled(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *dY, const void *W,
+                          const void *X_proj, void *dX, void *dW, void *dbias, void *ws, size_t ws_bytes,
+                          void *stream, int stage, void *ev_begin, void *ev_end);
+
+/* Test hooks for the bit-exactness requirement on the generator.
+ *
+ * rmm_debug_philox: out[4*t .. 4*t+3] (device, uint32) = Philox-4x32-10 of counter
+ * (c0 + t, c1, offset lo, offset hi) under the key of state.seed, t = 0..ncalls-1
+ * (c0 + t wraps modulo 2^32).
+ *
+ * rmm_debug_sketch_tile: P_out[r*cols + c] (device, fp32) = P[i0 + r][j0 + c], the
+ * UNSCALED sketch entry exactly as the fp32 kernels generate it, for 0 <= r < rows,
+ * 0 <= c < cols.  For Rademacher the values are exactly +1 / -1. */
+int rmm_debug_philox(rmm_rng_state_t state, uint32_t c0, uint32_t c1, int64_t ncalls, uint32_t *out,
+                     void *stream);
+int rmm_debug_sketch_tile(int kind, rmm_rng_state_t state, int64_t i0, int64_t j0, int64_t rows,
+                          int64_t cols, float *P_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RMM_H_ */

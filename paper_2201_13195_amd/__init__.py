@@ -1,0 +1,10 @@
+"""RMM linear layer (arXiv 2201.13195, Algorithm 1) for AMD MI355X.
+
+The arithmetic lives in librmm.so (hand-written HIP for gfx950, C ABI in
+include/rmm.h).  This package only marshals arguments: PyTorch tensors supply
+device memory and the current stream.
+"""
+from .binding import (  # noqa: F401
+    GAUSSIAN, RADEMACHER, RmmError, lib_path, load_library, rmm_backward, rmm_debug_philox,
+    rmm_debug_sketch_tile, rmm_forward, rmm_sketch, rmm_status_string, rmm_version, rmm_workspace_bytes,
+)

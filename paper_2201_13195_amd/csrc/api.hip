@@ -1,0 +1,225 @@
+// C ABI of the RMM linear layer: argument checks, workspace layout, dispatch.
+// Semantics of every entry point are stated in include/rmm.h.
+#include "../../include/rmm.h"
+
+#include <math.h>
+
+#include "common.hpp"
+
+using namespace rmm;
+
+namespace {
+
+constexpr int64_t kMaxDim = (int64_t)1 << 31;
+constexpr int64_t kMaxElems = (int64_t)1 << 40;
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline size_t elem_bytes(int dtype) { return dtype == RMM_DTYPE_BF16 ? 2 : 4; }
+
+bool dims_ok(int64_t a, int64_t b) { return a >= 1 && b >= 1 && a < kMaxDim && b < kMaxDim && a * b < kMaxElems; }
+
+bool desc_ok(const rmm_layer_desc_t *d) {
+    if (d == nullptr) return false;
+    if (d->dtype != RMM_DTYPE_F32 && d->dtype != RMM_DTYPE_BF16) return false;
+    if (d->kind != RMM_SKETCH_GAUSSIAN && d->kind != RMM_SKETCH_RADEMACHER) return false;
+    return dims_ok(d->n, d->d_in) && dims_ok(d->n, d->d_out) && dims_ok(d->d_out, d->d_in) &&
+           dims_ok(d->k, d->d_in) && dims_ok(d->k, d->d_out) && dims_ok(d->n, d->k);
+}
+
+// The plain kernels put the row tile index in gridDim.y.
+bool grid_ok(int64_t rows) { return (rows + 63) / 64 <= 65535; }
+
+// Workspace layout.  Backward: G = S^T dY (k x d_out, in the layer's dtype).
+size_t ws_backward(const rmm_layer_desc_t *d) { return round_up((size_t)d->k * d->d_out * elem_bytes(d->dtype), 256); }
+size_t ws_forward(const rmm_layer_desc_t *) { return 0; }
+size_t ws_sketch(const rmm_layer_desc_t *) { return 0; }
+
+int from_hip(hipError_t e) { return e == hipSuccess ? RMM_OK : RMM_ERR_LAUNCH; }
+
+// Optional pair of caller-owned events bracketing one stage of a pass.
+struct StageEvents {
+    int stage = RMM_STAGE_NONE;
+    hipEvent_t begin = nullptr, end = nullptr;
+};
+
+// Records the begin event on construction and the end event on destruction when
+// `stage` is the one being timed.
+class StageScope {
+public:
+    StageScope(const StageEvents &ev, int stage, hipStream_t stream)
+        : ev_(ev), on_(ev.stage == stage && ev.begin != nullptr && ev.end != nullptr), stream_(stream) {
+        if (on_) (void)hipEventRecord(ev_.begin, stream_);
+    }
+    ~StageScope() {
+        if (on_) (void)hipEventRecord(ev_.end, stream_);
+    }
+
+private:
+    const StageEvents &ev_;
+    bool on_;
+    hipStream_t stream_;
+};
+
+template <typename T>
+int sketch_impl(int64_t n, int64_t d, int64_t k, int kind, SketchState st, const void *A, void *out,
+                hipStream_t stream) {
+    const float alpha = 1.0f / sqrtf((float)k);
+    return from_hip(launch_sketch_plain<T, T>((const T *)A, (T *)out, n, d, k, kind, st, alpha, stream));
+}
+
+template <typename T>
+int forward_impl(const rmm_layer_desc_t *d, SketchState st, const void *X, const void *W, const void *bias, void *Y,
+                 void *X_proj, hipStream_t stream, const StageEvents &ev) {
+    {   // Y = X W^T (+ bias): A = X (n x d_in), B(kk, c) = W[c][kk].
+        StageScope scope(ev, RMM_STAGE_FWD_Y, stream);
+        hipError_t e = launch_gemm_plain<T, T>((const T *)X, d->d_in, 1, (const T *)W, 1, d->d_in, (T *)Y, d->d_out,
+                                               (const T *)bias, d->n, d->d_out, d->d_in, 1.0f, stream);
+        if (e != hipSuccess) return RMM_ERR_LAUNCH;
+    }
+    StageScope scope(ev, RMM_STAGE_FWD_XPROJ, stream);
+    return sketch_impl<T>(d->n, d->d_in, d->k, d->kind, st, X, X_proj, stream);
+}
+
+template <typename T>
+int backward_impl(const rmm_layer_desc_t *d, SketchState st, const void *dY, const void *W, const void *X_proj,
+                  void *dX, void *dW, void *dbias, void *ws, hipStream_t stream, const StageEvents &ev) {
+    hipError_t e;
+    if (dX != nullptr) {  // dX = dY W: B(kk, c) = W[kk][c]
+        StageScope scope(ev, RMM_STAGE_BWD_DX, stream);
+        e = launch_gemm_plain<T, T>((const T *)dY, d->d_out, 1, (const T *)W, d->d_in, 1, (T *)dX, d->d_in,
+                                    (const T *)nullptr, d->n, d->d_in, d->d_out, 1.0f, stream);
+        if (e != hipSuccess) return RMM_ERR_LAUNCH;
+    }
+    T *G = (T *)ws;  // G = S^T dY, k x d_out
+    {
+        StageScope scope(ev, RMM_STAGE_BWD_G, stream);
+        int rc = sketch_impl<T>(d->n, d->d_out, d->k, d->kind, st, dY, G, stream);
+        if (rc != RMM_OK) return rc;
+    }
+    {   // dW = G^T X_proj: A(r, kk) = G[kk][r], B(kk, c) = X_proj[kk][c]
+        StageScope scope(ev, RMM_STAGE_BWD_DW, stream);
+        e = launch_gemm_plain<T, T>(G, 1, d->d_out, (const T *)X_proj, d->d_in, 1, (T *)dW, d->d_in,
+                                    (const T *)nullptr, d->d_out, d->d_in, d->k, 1.0f, stream);
+        if (e != hipSuccess) return RMM_ERR_LAUNCH;
+    }
+    if (dbias != nullptr) {
+        StageScope scope(ev, RMM_STAGE_BWD_DBIAS, stream);
+        e = launch_colsum<T>((const T *)dY, (T *)dbias, d->n, d->d_out, stream);
+        if (e != hipSuccess) return RMM_ERR_LAUNCH;
+    }
+    return RMM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rmm_version(void) { return 100; }
+
+const char *rmm_status_string(int status) {
+    switch (status) {
+        case RMM_OK: return "ok";
+        case RMM_ERR_INVALID_ARG: return "invalid argument";
+        case RMM_ERR_UNSUPPORTED: return "size beyond the supported limits";
+        case RMM_ERR_WORKSPACE: return "workspace missing or too small";
+        case RMM_ERR_LAUNCH: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+size_t rmm_workspace_bytes(const rmm_layer_desc_t *desc, int op) {
+    if (desc == nullptr) return 0;
+    rmm_layer_desc_t d = *desc;
+    if (op == RMM_OP_SKETCH) d.d_out = d.d_in;
+    if (!desc_ok(&d)) return 0;
+    switch (op) {
+        case RMM_OP_FORWARD: return ws_forward(&d);
+        case RMM_OP_BACKWARD: return ws_backward(&d);
+        case RMM_OP_SKETCH: return ws_sketch(&d);
+        default: return 0;
+    }
+}
+
+int rmm_sketch(int64_t n, int64_t d, int64_t k, int dtype, int kind, rmm_rng_state_t state, const void *A,
+               void *A_proj, void *ws, size_t ws_bytes, void *stream) {
+    rmm_layer_desc_t desc = {n, d, d, k, dtype, kind};
+    if (!desc_ok(&desc) || A == nullptr || A_proj == nullptr) return RMM_ERR_INVALID_ARG;
+    if (!aligned16(A) || !aligned16(A_proj) || !aligned16(ws)) return RMM_ERR_INVALID_ARG;
+    if (!grid_ok(k)) return RMM_ERR_UNSUPPORTED;
+    const size_t need = ws_sketch(&desc);
+    if (need > 0 && (ws == nullptr || ws_bytes < need)) return RMM_ERR_WORKSPACE;
+    const SketchState st = make_state(state.seed, state.offset);
+    hipStream_t s = (hipStream_t)stream;
+    return dtype == RMM_DTYPE_BF16 ? sketch_impl<bf16_t>(n, d, k, kind, st, A, A_proj, s)
+                                   : sketch_impl<float>(n, d, k, kind, st, A, A_proj, s);
+}
+
+int rmm_forward_profiled(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *X, const void *W,
+                         const void *bias, void *Y, void *X_proj, void *ws, size_t ws_bytes, void *stream, int stage,
+                         void *ev_begin, void *ev_end) {
+    if (!desc_ok(desc) || X == nullptr || W == nullptr || Y == nullptr || X_proj == nullptr)
+        return RMM_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || !aligned16(X_proj) || !aligned16(ws))
+        return RMM_ERR_INVALID_ARG;
+    if (!grid_ok(desc->n) || !grid_ok(desc->k)) return RMM_ERR_UNSUPPORTED;
+    const size_t need = ws_forward(desc);
+    if (need > 0 && (ws == nullptr || ws_bytes < need)) return RMM_ERR_WORKSPACE;
+    const SketchState st = make_state(state.seed, state.offset);
+    hipStream_t s = (hipStream_t)stream;
+    StageEvents ev;
+    ev.stage = stage;
+    ev.begin = (hipEvent_t)ev_begin;
+    ev.end = (hipEvent_t)ev_end;
+    return desc->dtype == RMM_DTYPE_BF16 ? forward_impl<bf16_t>(desc, st, X, W, bias, Y, X_proj, s, ev)
+                                         : forward_impl<float>(desc, st, X, W, bias, Y, X_proj, s, ev);
+}
+
+int rmm_forward(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *X, const void *W, const void *bias,
+                void *Y, void *X_proj, void *ws, size_t ws_bytes, void *stream) {
+    return rmm_forward_profiled(desc, state, X, W, bias, Y, X_proj, ws, ws_bytes, stream, RMM_STAGE_NONE, nullptr,
+                                nullptr);
+}
+
+int rmm_backward_profiled(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *dY, const void *W,
+                          const void *X_proj, void *dX, void *dW, void *dbias, void *ws, size_t ws_bytes,
+                          void *stream, int stage, void *ev_begin, void *ev_end) {
+    if (!desc_ok(desc) || dY == nullptr || W == nullptr || X_proj == nullptr || dW == nullptr)
+        return RMM_ERR_INVALID_ARG;
+    if (!aligned16(dY) || !aligned16(W) || !aligned16(X_proj) || !aligned16(dX) || !aligned16(dW) || !aligned16(ws))
+        return RMM_ERR_INVALID_ARG;
+    if (!grid_ok(desc->n) || !grid_ok(desc->k) || !grid_ok(desc->d_out)) return RMM_ERR_UNSUPPORTED;
+    const size_t need = ws_backward(desc);
+    if (need > 0 && (ws == nullptr || ws_bytes < need)) return RMM_ERR_WORKSPACE;
+    const SketchState st = make_state(state.seed, state.offset);
+    hipStream_t s = (hipStream_t)stream;
+    StageEvents ev;
+    ev.stage = stage;
+    ev.begin = (hipEvent_t)ev_begin;
+    ev.end = (hipEvent_t)ev_end;
+    return desc->dtype == RMM_DTYPE_BF16 ? backward_impl<bf16_t>(desc, st, dY, W, X_proj, dX, dW, dbias, ws, s, ev)
+                                         : backward_impl<float>(desc, st, dY, W, X_proj, dX, dW, dbias, ws, s, ev);
+}
+
+int rmm_backward(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *dY, const void *W,
+                 const void *X_proj, void *dX, void *dW, void *dbias, void *ws, size_t ws_bytes, void *stream) {
+    return rmm_backward_profiled(desc, state, dY, W, X_proj, dX, dW, dbias, ws, ws_bytes, stream, RMM_STAGE_NONE,
+                                 nullptr, nullptr);
+}
+
+int rmm_debug_philox(rmm_rng_state_t state, uint32_t c0, uint32_t c1, int64_t ncalls, uint32_t *out, void *stream) {
+    if (out == nullptr || ncalls < 1 || ncalls >= kMaxDim) return RMM_ERR_INVALID_ARG;
+    return from_hip(
+        launch_debug_philox(make_state(state.seed, state.offset), c0, c1, ncalls, out, (hipStream_t)stream));
+}
+
+int rmm_debug_sketch_tile(int kind, rmm_rng_state_t state, int64_t i0, int64_t j0, int64_t rows, int64_t cols,
+                          float *P_out, void *stream) {
+    if (P_out == nullptr || rows < 1 || cols < 1 || i0 < 0 || j0 < 0) return RMM_ERR_INVALID_ARG;
+    if (kind != RMM_SKETCH_GAUSSIAN && kind != RMM_SKETCH_RADEMACHER) return RMM_ERR_INVALID_ARG;
+    if (!dims_ok(rows, cols) || i0 + rows > kMaxDim || j0 + cols > kMaxDim) return RMM_ERR_UNSUPPORTED;
+    return from_hip(launch_debug_sketch_tile(kind, make_state(state.seed, state.offset), i0, j0, rows, cols, P_out,
+                                             (hipStream_t)stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,60 @@
+// Shared device helpers and the host-side launcher declarations of the library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "philox.hpp"
+
+namespace rmm {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t x) { return __uint_as_float((uint32_t)x << 16); }
+
+// Round to nearest even; NaN stays NaN (quiet).
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (bf16_t)((u >> 16) | 0x0040u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+template <typename T>
+__device__ __forceinline__ float load_f32(const T *p);
+template <>
+__device__ __forceinline__ float load_f32<float>(const float *p) { return *p; }
+template <>
+__device__ __forceinline__ float load_f32<bf16_t>(const bf16_t *p) { return bf16_to_f32(*p); }
+
+template <typename T>
+__device__ __forceinline__ void store_f32(T *p, float v);
+template <>
+__device__ __forceinline__ void store_f32<float>(float *p, float v) { *p = v; }
+template <>
+__device__ __forceinline__ void store_f32<bf16_t>(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+
+// ---------------------------------------------------------------------------
+// Host launchers (each returns the hipError_t of its launches).
+// ---------------------------------------------------------------------------
+
+// Plain LDS-tiled fp32-FMA kernels: the fp32 data path, and a slow bf16 one.
+//   C[m x n] = alpha * A * B (+ bias[n] per row), A(m,kk) at A[m*sam + kk*sak],
+//   B(kk,n) at B[kk*sbk + n*sbn], C row-major with leading dimension ldc.
+template <typename Tin, typename Tout>
+hipError_t launch_gemm_plain(const Tin *A, int64_t sam, int64_t sak, const Tin *B, int64_t sbk, int64_t sbn,
+                             Tout *C, int64_t ldc, const Tin *bias, int64_t m, int64_t n, int64_t kk, float alpha,
+                             hipStream_t stream);
+//   out[k x d] = alpha * P^T A with P the unscaled sketch (n x k) of `st`.
+template <typename Tin, typename Tout>
+hipError_t launch_sketch_plain(const Tin *A, Tout *out, int64_t n, int64_t d, int64_t k, int kind, SketchState st,
+                               float alpha, hipStream_t stream);
+//   out[d] = column sums of A[n x d].
+template <typename T>
+hipError_t launch_colsum(const T *A, T *out, int64_t n, int64_t d, hipStream_t stream);
+
+hipError_t launch_debug_philox(SketchState st, uint32_t c0, uint32_t c1, int64_t ncalls, uint32_t *out,
+                               hipStream_t stream);
+hipError_t launch_debug_sketch_tile(int kind, SketchState st, int64_t i0, int64_t j0, int64_t rows, int64_t cols,
+                                    float *out, hipStream_t stream);
+
+}  // namespace rmm

@@ -1,0 +1,99 @@
+"""CPU-only checks of the C boundary: the built library exports every function
+include/rmm.h declares, and argument errors are reported as status codes before
+any GPU work is attempted."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+import paper_2201_13195_amd as rmm
+from paper_2201_13195_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(rmm.lib_path()):
+        from paper_2201_13195_amd import build
+        build.build()
+    return rmm.load_library()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "rmm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rmm_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert {"rmm_forward", "rmm_backward", "rmm_sketch", "rmm_workspace_bytes", "rmm_status_string",
+            "rmm_debug_philox", "rmm_debug_sketch_tile", "rmm_version"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(lib):
+    seen = {rmm.rmm_status_string(s) for s in (0, -1, -2, -3, -4)}
+    assert len(seen) == 5
+    assert rmm.rmm_status_string(-99) == "unknown status"
+    assert rmm.rmm_version() >= 100
+
+
+def test_workspace_query(lib):
+    assert rmm.rmm_workspace_bytes(4096, 768, 3072, 410, torch.bfloat16, rmm.GAUSSIAN, binding.OP_BACKWARD) \
+        >= 410 * 3072 * 2
+    assert rmm.rmm_workspace_bytes(256, 128, 128, 32, torch.float32, rmm.GAUSSIAN, binding.OP_BACKWARD) \
+        >= 32 * 128 * 4
+    # invalid descriptors -> 0
+    assert rmm.rmm_workspace_bytes(0, 768, 3072, 410, torch.bfloat16, 0, binding.OP_BACKWARD) == 0
+    assert rmm.rmm_workspace_bytes(4096, 768, 3072, 410, torch.bfloat16, 7, binding.OP_BACKWARD) == 0
+    assert rmm.rmm_workspace_bytes(4096, 768, 3072, 410, torch.bfloat16, 0, 9) == 0
+    assert lib.rmm_workspace_bytes(None, 0) == 0
+
+
+def test_invalid_arguments_are_status_codes(lib):
+    """Every call here fails validation, so nothing is launched (no GPU needed)."""
+    D, S = binding._Desc, binding._State
+    st = S(1, 2)
+    good = D(64, 32, 32, 8, 0, 0)
+    fake = ctypes.c_void_p(0x1000)       # aligned, never dereferenced: validation fails first
+    odd = ctypes.c_void_p(0x1004)
+    assert lib.rmm_forward(None, st, fake, fake, None, fake, fake, None, 0, None) == -1
+    assert lib.rmm_forward(ctypes.byref(good), st, None, fake, None, fake, fake, None, 0, None) == -1
+    assert lib.rmm_forward(ctypes.byref(good), st, odd, fake, None, fake, fake, None, 0, None) == -1
+    for bad in (D(0, 32, 32, 8, 0, 0), D(64, -1, 32, 8, 0, 0), D(64, 32, 32, 0, 0, 0), D(64, 32, 32, 8, 5, 0),
+                D(64, 32, 32, 8, 0, 3), D(1 << 31, 32, 32, 8, 0, 0)):
+        assert lib.rmm_forward(ctypes.byref(bad), st, fake, fake, None, fake, fake, None, 0, None) == -1
+        assert lib.rmm_backward(ctypes.byref(bad), st, fake, fake, fake, fake, fake, None, None, 0, None) == -1
+    assert lib.rmm_backward(ctypes.byref(good), st, fake, fake, fake, fake, None, None, None, 0, None) == -1
+    # workspace missing / too small
+    assert lib.rmm_backward(ctypes.byref(good), st, fake, fake, fake, fake, fake, None, None, 0, None) == -3
+    assert lib.rmm_backward(ctypes.byref(good), st, fake, fake, fake, fake, fake, None, fake, 8, None) == -3
+    assert lib.rmm_sketch(0, 4, 4, 0, 0, st, fake, fake, None, 0, None) == -1
+    assert lib.rmm_sketch(8, 4, 4, 0, 0, st, None, fake, None, 0, None) == -1
+    assert lib.rmm_sketch(8, 4, 4, 2, 0, st, fake, fake, None, 0, None) == -1
+    assert lib.rmm_debug_philox(st, 0, 0, 0, fake, None) == -1
+    assert lib.rmm_debug_philox(st, 0, 0, 4, None, None) == -1
+    assert lib.rmm_debug_sketch_tile(0, st, -1, 0, 4, 4, fake, None) == -1
+    assert lib.rmm_debug_sketch_tile(2, st, 0, 0, 4, 4, fake, None) == -1
+
+
+def test_binding_refuses_cpu_tensors(lib):
+    X = torch.zeros(8, 4)
+    W = torch.zeros(4, 4)
+    with pytest.raises(ValueError):
+        rmm.rmm_forward(X, W, None, 2, rmm.GAUSSIAN, 0, 0,
+                        Y=torch.zeros(8, 4), X_proj=torch.zeros(2, 4), ws=torch.zeros(16, dtype=torch.uint8))
+
+
+def test_product_package_does_not_touch_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2201_13195_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text, os.path.join(dirpath, f)

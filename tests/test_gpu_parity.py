@@ -1,0 +1,179 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle on
+identical seeded inputs.  Integer work (Philox words, Rademacher signs) must be
+bit-exact; Y, X_proj, dX, dW must agree to a relative Frobenius error of 1e-5
+(fp32) / 1e-2 (bf16)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2201_13195_amd as rmm
+from paper_2201_13195_amd import synth
+from oracle import philox as o_philox
+from oracle import rmm as o_rmm
+from oracle import sketch as o_sketch
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 1e-2}
+DEV = "cuda"
+
+
+def rel_fro(got, want):
+    got = synth.to_f64(got) if isinstance(got, torch.Tensor) else got
+    return float(np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-300))
+
+
+def run_layer(X, W, dY, k, kind, seed, offset, bias=None):
+    """One forward + backward through the library; returns GPU tensors."""
+    Xd, Wd, dYd = X.to(DEV), W.to(DEV), dY.to(DEV)
+    bd = None if bias is None else bias.to(DEV)
+    Y, Xp = rmm.rmm_forward(Xd, Wd, bd, k, kind, seed, offset)
+    dX, dW, db = rmm.rmm_backward(dYd, Wd, Xp, kind, seed, offset, need_dbias=bias is not None)
+    torch.cuda.synchronize()
+    return Y, Xp, dX, dW, db
+
+
+def check_layer(X, W, dY, k, kind, seed, offset, dtype, bias=None, label=""):
+    Y, Xp, dX, dW, db = run_layer(X, W, dY, k, kind, seed, offset, bias)
+    X64, W64, dY64 = synth.to_f64(X), synth.to_f64(W), synth.to_f64(dY)
+    b64 = None if bias is None else synth.to_f64(bias)
+    oY, oXp = o_rmm.forward(X64, W64, b64, k, kind, seed, offset)
+    # the backward oracle gets the X_proj the device layer actually saved, as the real backward call does
+    odX, odW, odb = o_rmm.backward(dY64, W64, synth.to_f64(Xp), kind, seed, offset)
+    # ... and also the fully chained oracle value, which the saved X_proj must reproduce
+    _, odW_chain, _ = o_rmm.backward(dY64, W64, oXp, kind, seed, offset)
+    tol = TOL[dtype]
+    errs = {"Y": rel_fro(Y, oY), "X_proj": rel_fro(Xp, oXp), "dX": rel_fro(dX, odX), "dW": rel_fro(dW, odW),
+            "dW_chain": rel_fro(dW, odW_chain)}
+    if bias is not None:
+        errs["db"] = rel_fro(db, odb)
+    print(label, {k_: "%.2e" % v for k_, v in errs.items()}, flush=True)
+    for name, e in errs.items():
+        assert e <= tol, (label, name, e)
+    return errs
+
+
+# ----------------------------------------------------------------------------- generator, bit-exact
+
+def test_philox_words_bit_exact():
+    cases = [(0, 0, 0, 0, 1000), (0x0123456789ABCDEF, (7 << 32) | 5, 12345, 77, 4099),
+             (2 ** 64 - 1, 2 ** 64 - 1, 2 ** 32 - 3, 2 ** 32 - 1, 10)]      # last: c0 wraps past 2^32
+    for seed, offset, c0, c1, ncalls in cases:
+        got = rmm.rmm_debug_philox(seed, offset, c0, c1, ncalls).cpu().numpy().view(np.uint32)
+        t = np.arange(ncalls, dtype=np.uint64)
+        want = np.stack(o_philox.philox4x32_10((c0 + t) & 0xFFFFFFFF, c1, offset & 0xFFFFFFFF, offset >> 32,
+                                               seed & 0xFFFFFFFF, seed >> 32), axis=1)
+        assert np.array_equal(got, want)
+
+
+def test_philox_known_answers_on_device():
+    """Published vector: counter 0, key 0 -> 6627e8d5 e169c58d bc57ac4c 9b00dbd8."""
+    got = rmm.rmm_debug_philox(0, 0, 0, 0, 1).cpu().numpy().view(np.uint32)[0]
+    assert [hex(int(x)) for x in got] == ["0x6627e8d5", "0xe169c58d", "0xbc57ac4c", "0x9b00dbd8"]
+
+
+@pytest.mark.parametrize("i0,j0,rows,cols", [(0, 0, 300, 7), (100, 3, 200, 65), (127, 1000, 3, 2), (4090, 0, 6, 410)])
+def test_rademacher_signs_bit_exact(i0, j0, rows, cols):
+    seed, offset = 0xFEEDFACE12345678, 3
+    got = rmm.rmm_debug_sketch_tile(rmm.RADEMACHER, seed, offset, i0, j0, rows, cols).cpu().numpy()
+    want = o_sketch.sketch_P(i0 + rows, j0 + cols, o_sketch.RADEMACHER, seed, offset)[i0:, j0:]
+    assert np.array_equal(got.astype(np.float64), want)
+
+
+@pytest.mark.parametrize("i0,j0,rows,cols", [(0, 0, 64, 16), (5, 9, 131, 33), (16380, 1630, 4, 8)])
+def test_gaussian_tile_fp32(i0, j0, rows, cols):
+    seed, offset = 0xFEEDFACE12345678, 1 << 33
+    got = rmm.rmm_debug_sketch_tile(rmm.GAUSSIAN, seed, offset, i0, j0, rows, cols).cpu().numpy().astype(np.float64)
+    want = o_sketch.sketch_P(i0 + rows, j0 + cols, o_sketch.GAUSSIAN, seed, offset)[i0:, j0:]
+    assert np.abs(got - want).max() < 4e-6
+    assert rel_fro(got, want) < 1e-6
+
+
+# ----------------------------------------------------------------------------- layer parity
+
+def test_config1_fp32():
+    c = synth.CONFIGS["c1_fp32_small"]
+    X, W, dY = synth.config_inputs("c1_fp32_small")
+    check_layer(X, W, dY, c["k"], rmm.GAUSSIAN, c["seed"], 0, "f32", label="c1")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("kind", [rmm.GAUSSIAN, rmm.RADEMACHER])
+@pytest.mark.parametrize("shape", [(333, 200, 136, 77), (130, 72, 264, 129), (1, 8, 8, 1), (9, 16, 24, 40),
+                                   (257, 101, 67, 19), (1000, 8, 520, 5)])
+def test_small_and_ragged(dtype, kind, shape):
+    """Several tiles plus ragged tails in every dimension; n not a multiple of the
+    generator's block (8 / 128 tokens); k = 1; k > n; odd widths."""
+    n, d_in, d_out, k = shape
+    X, W, dY = synth.layer_inputs(n, d_in, d_out, dtype, (11, 12, 13), w_std=1.0 / math.sqrt(d_in))
+    bias = synth.to_torch(synth.normal((d_out,), 14), dtype)
+    check_layer(X, W, dY, k, kind, 0xABCDEF, 42, dtype, bias=bias, label="ragged %s %s %s" % (shape, dtype, kind))
+
+
+def test_config2_base_attention():
+    c = synth.CONFIGS["c2_base_attn"]
+    X, W, dY = synth.config_inputs("c2_base_attn")
+    check_layer(X, W, dY, c["k"], rmm.GAUSSIAN, c["seed"], 0, "bf16", label="c2")
+
+
+@pytest.mark.parametrize("kind", [rmm.GAUSSIAN, rmm.RADEMACHER])
+@pytest.mark.parametrize("rho", [0.1, 0.2, 0.5, 0.9])
+@pytest.mark.parametrize("name,offset", [("c3_base_ffn_up", 0), ("c3_base_ffn_down", 1)])
+def test_config3_base_ffn_sweep(name, offset, rho, kind):
+    c = synth.CONFIGS[name]
+    k = synth.sketch_size(rho, c["n"])
+    assert k in (410, 819, 2048, 3686)
+    X, W, dY = synth.config_inputs(name)
+    check_layer(X, W, dY, k, kind, c["seed"], offset, "bf16", label="%s rho=%s kind=%d" % (name, rho, kind))
+
+
+@pytest.mark.parametrize("name,offset", [("c4_large_attn", 0), ("c4_large_ffn_up", 1), ("c4_large_ffn_down", 2)])
+def test_config4_large(name, offset):
+    c = synth.CONFIGS[name]
+    assert c["k"] == synth.sketch_size(0.1, c["n"]) == 1638
+    X, W, dY = synth.config_inputs(name)
+    check_layer(X, W, dY, c["k"], rmm.GAUSSIAN, c["seed"], offset, "bf16", label=name)
+
+
+# ----------------------------------------------------------------------------- contracts of the boundary
+
+def test_forward_and_sketch_agree_and_are_deterministic():
+    X, W, dY = synth.layer_inputs(700, 256, 128, "bf16", (21, 22, 23))
+    Xd, Wd, dYd = X.to(DEV), W.to(DEV), dY.to(DEV)
+    for kind in (rmm.GAUSSIAN, rmm.RADEMACHER):
+        Y1, Xp1 = rmm.rmm_forward(Xd, Wd, None, 96, kind, 5, 6)
+        Y2, Xp2 = rmm.rmm_forward(Xd, Wd, None, 96, kind, 5, 6)
+        Xp3 = rmm.rmm_sketch(Xd, 96, kind, 5, 6)
+        assert torch.equal(Y1, Y2) and torch.equal(Xp1, Xp2) and torch.equal(Xp1, Xp3)
+        d1 = rmm.rmm_backward(dYd, Wd, Xp1, kind, 5, 6)
+        d2 = rmm.rmm_backward(dYd, Wd, Xp1, kind, 5, 6)
+        assert torch.equal(d1[0], d2[0]) and torch.equal(d1[1], d2[1])
+        # another offset / seed is another sketch
+        assert not torch.equal(Xp1, rmm.rmm_sketch(Xd, 96, kind, 5, 7))
+        assert not torch.equal(Xp1, rmm.rmm_sketch(Xd, 96, kind, 4, 6))
+        # dX can be skipped
+        dX, dW, _ = rmm.rmm_backward(dYd, Wd, Xp1, kind, 5, 6, need_dX=False)
+        assert dX is None and torch.equal(dW, d1[1])
+
+
+def test_saved_bytes_ratio_is_k_over_n():
+    """Section 2.4.1: what the layer keeps is X_proj (k x d_in) + 16 bytes."""
+    for name in ("c2_base_attn", "c4_large_ffn_down"):
+        c = synth.CONFIGS[name]
+        Xp = torch.empty((c["k"], c["d_in"]), dtype=torch.bfloat16, device=DEV)
+        x_bytes = c["n"] * c["d_in"] * 2
+        assert Xp.numel() * Xp.element_size() * c["n"] == x_bytes * c["k"]
+        saved, plain = o_rmm.saved_bytes(c["n"], c["d_in"], c["k"], 2)
+        assert saved == Xp.numel() * 2 + 16 and plain == x_bytes
+
+
+def test_workspace_too_small_is_reported():
+    X, W, dY = synth.layer_inputs(64, 32, 32, "f32", (1, 2, 3))
+    Xd, Wd, dYd = X.to(DEV), W.to(DEV), dY.to(DEV)
+    _, Xp = rmm.rmm_forward(Xd, Wd, None, 8, rmm.GAUSSIAN, 0, 0)
+    small = torch.empty(16, dtype=torch.uint8, device=DEV)
+    with pytest.raises(rmm.RmmError) as e:
+        rmm.rmm_backward(dYd, Wd, Xp, rmm.GAUSSIAN, 0, 0, ws=small)
+    assert e.value.status == -3
