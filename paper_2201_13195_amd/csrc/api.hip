@@ -30,10 +30,21 @@ bool desc_ok(const rmm_layer_desc_t *d) {
 // The plain kernels put the row tile index in gridDim.y.
 bool grid_ok(int64_t rows) { return (rows + 63) / 64 <= 65535; }
 
-// Workspace layout.  Backward: G = S^T dY (k x d_out, in the layer's dtype).
-size_t ws_backward(const rmm_layer_desc_t *d) { return round_up((size_t)d->k * d->d_out * elem_bytes(d->dtype), 256); }
-size_t ws_forward(const rmm_layer_desc_t *) { return 0; }
-size_t ws_sketch(const rmm_layer_desc_t *) { return 0; }
+bool use_mfma(const rmm_layer_desc_t *d) {
+    return d->dtype == RMM_DTYPE_BF16 && mfma_shape_ok(d->n, d->d_in, d->d_out, d->k);
+}
+
+// Workspace layout.
+//   sketch / forward: fp32 partial sums of the token slices of S^T A (MFMA path only).
+//   backward: G = S^T dY (k x d_out, in the layer's dtype), then the partial sums.
+size_t g_bytes(const rmm_layer_desc_t *d) { return round_up((size_t)d->k * d->d_out * elem_bytes(d->dtype), 256); }
+size_t ws_sketch(const rmm_layer_desc_t *d) {
+    return use_mfma(d) ? round_up(sketch_workspace_bf16(d->n, d->d_in, d->k), 256) : 0;
+}
+size_t ws_forward(const rmm_layer_desc_t *d) { return ws_sketch(d); }
+size_t ws_backward(const rmm_layer_desc_t *d) {
+    return g_bytes(d) + (use_mfma(d) ? round_up(sketch_workspace_bf16(d->n, d->d_out, d->k), 256) : 0);
+}
 
 int from_hip(hipError_t e) { return e == hipSuccess ? RMM_OK : RMM_ERR_LAUNCH; }
 
@@ -62,45 +73,56 @@ private:
 };
 
 template <typename T>
-int sketch_impl(int64_t n, int64_t d, int64_t k, int kind, SketchState st, const void *A, void *out,
-                hipStream_t stream) {
+int sketch_impl(int64_t n, int64_t d, int64_t k, int kind, SketchState st, const void *A, void *out, bool mfma,
+                void *ws, hipStream_t stream) {
+    if (mfma)
+        return from_hip(launch_sketch_bf16((const bf16_t *)A, (bf16_t *)out, n, d, k, kind, st, ws, stream));
     const float alpha = 1.0f / sqrtf((float)k);
     return from_hip(launch_sketch_plain<T, T>((const T *)A, (T *)out, n, d, k, kind, st, alpha, stream));
 }
 
 template <typename T>
 int forward_impl(const rmm_layer_desc_t *d, SketchState st, const void *X, const void *W, const void *bias, void *Y,
-                 void *X_proj, hipStream_t stream, const StageEvents &ev) {
+                 void *X_proj, void *ws, hipStream_t stream, const StageEvents &ev) {
+    const bool mfma = use_mfma(d);
     {   // Y = X W^T (+ bias): A = X (n x d_in), B(kk, c) = W[c][kk].
         StageScope scope(ev, RMM_STAGE_FWD_Y, stream);
-        hipError_t e = launch_gemm_plain<T, T>((const T *)X, d->d_in, 1, (const T *)W, 1, d->d_in, (T *)Y, d->d_out,
-                                               (const T *)bias, d->n, d->d_out, d->d_in, 1.0f, stream);
+        hipError_t e =
+            mfma ? launch_linear_nt_bf16((const bf16_t *)X, (const bf16_t *)W, (const bf16_t *)bias, (bf16_t *)Y,
+                                         d->n, d->d_in, d->d_out, stream)
+                 : launch_gemm_plain<T, T>((const T *)X, d->d_in, 1, (const T *)W, 1, d->d_in, (T *)Y, d->d_out,
+                                           (const T *)bias, d->n, d->d_out, d->d_in, 1.0f, stream);
         if (e != hipSuccess) return RMM_ERR_LAUNCH;
     }
     StageScope scope(ev, RMM_STAGE_FWD_XPROJ, stream);
-    return sketch_impl<T>(d->n, d->d_in, d->k, d->kind, st, X, X_proj, stream);
+    return sketch_impl<T>(d->n, d->d_in, d->k, d->kind, st, X, X_proj, mfma, ws, stream);
 }
 
 template <typename T>
 int backward_impl(const rmm_layer_desc_t *d, SketchState st, const void *dY, const void *W, const void *X_proj,
                   void *dX, void *dW, void *dbias, void *ws, hipStream_t stream, const StageEvents &ev) {
     hipError_t e;
+    const bool mfma = use_mfma(d);
     if (dX != nullptr) {  // dX = dY W: B(kk, c) = W[kk][c]
         StageScope scope(ev, RMM_STAGE_BWD_DX, stream);
-        e = launch_gemm_plain<T, T>((const T *)dY, d->d_out, 1, (const T *)W, d->d_in, 1, (T *)dX, d->d_in,
-                                    (const T *)nullptr, d->n, d->d_in, d->d_out, 1.0f, stream);
+        e = mfma ? launch_linear_nn_bf16((const bf16_t *)dY, (const bf16_t *)W, (bf16_t *)dX, d->n, d->d_in, d->d_out,
+                                         stream)
+                 : launch_gemm_plain<T, T>((const T *)dY, d->d_out, 1, (const T *)W, d->d_in, 1, (T *)dX, d->d_in,
+                                           (const T *)nullptr, d->n, d->d_in, d->d_out, 1.0f, stream);
         if (e != hipSuccess) return RMM_ERR_LAUNCH;
     }
     T *G = (T *)ws;  // G = S^T dY, k x d_out
     {
         StageScope scope(ev, RMM_STAGE_BWD_G, stream);
-        int rc = sketch_impl<T>(d->n, d->d_out, d->k, d->kind, st, dY, G, stream);
+        int rc = sketch_impl<T>(d->n, d->d_out, d->k, d->kind, st, dY, G, mfma, (char *)ws + g_bytes(d), stream);
         if (rc != RMM_OK) return rc;
     }
     {   // dW = G^T X_proj: A(r, kk) = G[kk][r], B(kk, c) = X_proj[kk][c]
         StageScope scope(ev, RMM_STAGE_BWD_DW, stream);
-        e = launch_gemm_plain<T, T>(G, 1, d->d_out, (const T *)X_proj, d->d_in, 1, (T *)dW, d->d_in,
-                                    (const T *)nullptr, d->d_out, d->d_in, d->k, 1.0f, stream);
+        e = mfma ? launch_dw_bf16((const bf16_t *)G, (const bf16_t *)X_proj, (bf16_t *)dW, d->k, d->d_in, d->d_out,
+                                  stream)
+                 : launch_gemm_plain<T, T>(G, 1, d->d_out, (const T *)X_proj, d->d_in, 1, (T *)dW, d->d_in,
+                                           (const T *)nullptr, d->d_out, d->d_in, d->k, 1.0f, stream);
         if (e != hipSuccess) return RMM_ERR_LAUNCH;
     }
     if (dbias != nullptr) {
@@ -151,8 +173,9 @@ int rmm_sketch(int64_t n, int64_t d, int64_t k, int dtype, int kind, rmm_rng_sta
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return RMM_ERR_WORKSPACE;
     const SketchState st = make_state(state.seed, state.offset);
     hipStream_t s = (hipStream_t)stream;
-    return dtype == RMM_DTYPE_BF16 ? sketch_impl<bf16_t>(n, d, k, kind, st, A, A_proj, s)
-                                   : sketch_impl<float>(n, d, k, kind, st, A, A_proj, s);
+    const bool mfma = use_mfma(&desc);
+    return dtype == RMM_DTYPE_BF16 ? sketch_impl<bf16_t>(n, d, k, kind, st, A, A_proj, mfma, ws, s)
+                                   : sketch_impl<float>(n, d, k, kind, st, A, A_proj, false, ws, s);
 }
 
 int rmm_forward_profiled(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *X, const void *W,
@@ -171,8 +194,8 @@ int rmm_forward_profiled(const rmm_layer_desc_t *desc, rmm_rng_state_t state, co
     ev.stage = stage;
     ev.begin = (hipEvent_t)ev_begin;
     ev.end = (hipEvent_t)ev_end;
-    return desc->dtype == RMM_DTYPE_BF16 ? forward_impl<bf16_t>(desc, st, X, W, bias, Y, X_proj, s, ev)
-                                         : forward_impl<float>(desc, st, X, W, bias, Y, X_proj, s, ev);
+    return desc->dtype == RMM_DTYPE_BF16 ? forward_impl<bf16_t>(desc, st, X, W, bias, Y, X_proj, ws, s, ev)
+                                         : forward_impl<float>(desc, st, X, W, bias, Y, X_proj, ws, s, ev);
 }
 
 int rmm_forward(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *X, const void *W, const void *bias,

@@ -52,6 +52,19 @@ hipError_t launch_sketch_plain(const Tin *A, Tout *out, int64_t n, int64_t d, in
 template <typename T>
 hipError_t launch_colsum(const T *A, T *out, int64_t n, int64_t d, hipStream_t stream);
 
+// bf16 MFMA path (mfma.hip).  Usable when mfma_shape_ok(); `ws` for the sketch
+// must hold sketch_workspace_bf16() bytes (fp32 partial sums of the token slices).
+bool mfma_shape_ok(int64_t n, int64_t d_in, int64_t d_out, int64_t k);
+hipError_t launch_linear_nt_bf16(const bf16_t *X, const bf16_t *W, const bf16_t *bias, bf16_t *Y, int64_t n,
+                                 int64_t d_in, int64_t d_out, hipStream_t stream);
+hipError_t launch_linear_nn_bf16(const bf16_t *dY, const bf16_t *W, bf16_t *dX, int64_t n, int64_t d_in,
+                                 int64_t d_out, hipStream_t stream);
+hipError_t launch_dw_bf16(const bf16_t *G, const bf16_t *X_proj, bf16_t *dW, int64_t k, int64_t d_in, int64_t d_out,
+                          hipStream_t stream);
+size_t sketch_workspace_bf16(int64_t n, int64_t d, int64_t k);
+hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d, int64_t k, int kind, SketchState st,
+                              void *ws, hipStream_t stream);
+
 hipError_t launch_debug_philox(SketchState st, uint32_t c0, uint32_t c1, int64_t ncalls, uint32_t *out,
                                hipStream_t stream);
 hipError_t launch_debug_sketch_tile(int kind, SketchState st, int64_t i0, int64_t j0, int64_t rows, int64_t cols,
