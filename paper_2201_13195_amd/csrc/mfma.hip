@@ -31,6 +31,7 @@ typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 enum { A_KCONTIG = 0, A_MCONTIG = 1, A_GAUSS = 2, A_RADEM = 3 };
 enum { B_KCONTIG = 0, B_NCONTIG = 1 };
@@ -48,17 +49,12 @@ struct GemmArgs {
     int64_t ldc;
     const bf16_t *bias;
     int64_t M, N, K;
+    int64_t a_bytes, b_bytes;  // byte sizes of the A and B operands in memory (each below 2^31)
     float alpha;
     SketchState st;
     int64_t k_chunk;       // contraction elements per blockIdx.z slice (multiple of 128)
     int64_t split_stride;  // fp32 elements between the partial results of two slices
 };
-
-__device__ __forceinline__ uint4 ld16(const bf16_t *p, bool pred) {
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (pred) v = *reinterpret_cast<const uint4 *>(p);
-    return v;
-}
 
 // Eight unscaled Gaussian entries P[8*c0 .. 8*c0+7][j] as a bf16 MFMA operand.
 __device__ __forceinline__ bf16x8_t gauss_operand(const SketchState &st, uint32_t c0, uint32_t j) {
@@ -141,18 +137,31 @@ __device__ __forceinline__ bf16x8_t frag_transposed(const bf16_t *tile, int stri
     return out.v;
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int AMODE, int BMODE, int OUT>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int AMODE, int BMODE, int OUT, int D>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_mfma_kernel(GemmArgs g) {
     typedef Tile<BM, BN, BK, WAVES_M, WAVES_N, AMODE, BMODE, OUT> T;
     __shared__ __attribute__((aligned(16))) bf16_t lds[2 * T::STAGE_ELEMS];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-    const int64_t tiles_n = (g.N + BN - 1) / BN;
-    const int64_t m0 = (int64_t)(blockIdx.x / tiles_n) * BM, n0 = (int64_t)(blockIdx.x % tiles_n) * BN;
+    // Tile order.  Work-groups are dealt round-robin to the 8 XCDs (each with its own L2), so first
+    // renumber them such that one XCD owns a contiguous run of positions; then walk the tile grid
+    // in bands of GROUP_M tile rows, column by column, so that the work-groups resident on one XCD
+    // at the same time form a compact block that shares A row blocks and B column blocks in L2.
+    const int64_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    const int64_t tiles = (int64_t)gridDim.x;
+    int64_t tile = blockIdx.x;
+    {
+        const int64_t per = tiles / 8, rem = tiles % 8, x = tile % 8, r = tile / 8;
+        tile = x * per + (x < rem ? x : rem) + r;   // XCD x owns `per` (+1 for the first `rem`) consecutive positions
+    }
+    constexpr int64_t GROUP_M = 8;
+    const int64_t band = tile / (GROUP_M * tiles_n), in_band = tile % (GROUP_M * tiles_n);
+    const int64_t band_rows = min(GROUP_M, tiles_m - band * GROUP_M);
+    const int64_t m0 = (band * GROUP_M + in_band % band_rows) * BM, n0 = (in_band / band_rows) * BN;
     const int64_t kk_begin = (int64_t)blockIdx.z * g.k_chunk;
     const int64_t kk_end = min(g.K, kk_begin + g.k_chunk);
-    const int num_tiles = (int)((kk_end - kk_begin + BK - 1) / BK);
+    const int num_tiles = kk_end > kk_begin ? (int)((kk_end - kk_begin + BK - 1) / BK) : 0;
 
     f32x16_t acc[T::TM][T::TN];
 #pragma unroll
@@ -162,155 +171,240 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_mfma_kernel(GemmA
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
-    uint4 ra[T::A_CHUNKS > 0 ? T::A_CHUNKS : 1], rb[T::B_CHUNKS];
+    // Global loads are buffer loads: an offset at or beyond the operand's byte size returns zeros
+    // without touching memory, so tile edges and the tail of the contraction need no branches (a
+    // chunk that must read as zero is simply given the offset 2^31).  Matrices are below 2^31 bytes.
+    const __amdgpu_buffer_rsrc_t rsrc_a =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(g.A), (short)0, (int)g.a_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_b =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(g.B), (short)0, (int)g.b_bytes, 0x00020000);
+    constexpr uint32_t OOB = 0x80000000u;
 
-    auto load_global = [&](int64_t kk0) {
-        if constexpr (AMODE == A_KCONTIG) {  // A[m][kk], tile BM x BK
+    // Per 16-byte chunk of a tile: byte offset in the operand for the first tile of this slice,
+    // whether its row / column group exists at all, and its position along the contraction.
+    uint32_t a_off[T::A_CHUNKS > 0 ? T::A_CHUNKS : 1], b_off[T::B_CHUNKS];
+    bool a_ok[T::A_CHUNKS > 0 ? T::A_CHUNKS : 1], b_ok[T::B_CHUNKS];
+    int a_kk[T::A_CHUNKS > 0 ? T::A_CHUNKS : 1], b_kk[T::B_CHUNKS];
+    int a_lds[T::A_CHUNKS > 0 ? T::A_CHUNKS : 1], b_lds[T::B_CHUNKS];
+    uint32_t a_step = 0, b_step = 0;  // bytes per tile along the contraction
+    if constexpr (AMODE == A_KCONTIG) {  // A[m][kk], tile BM x BK
+        a_step = BK * 2;
+#pragma unroll
+        for (int q = 0; q < T::A_CHUNKS; ++q) {
+            const int c = tid + T::THREADS * q, row = c / (BK / 8), kc = c % (BK / 8);
+            a_ok[q] = m0 + row < g.M;
+            a_kk[q] = kc * 8;
+            a_off[q] = (uint32_t)(((m0 + row) * g.lda + kk_begin + kc * 8) * 2);
+            a_lds[q] = row * T::A_STRIDE + kc * 8;
+        }
+    } else if constexpr (AMODE == A_MCONTIG) {  // A stored [kk][m], tile BK x BM
+        a_step = (uint32_t)(BK * g.lda * 2);
+#pragma unroll
+        for (int q = 0; q < T::A_CHUNKS; ++q) {
+            const int c = tid + T::THREADS * q, row = c / (BM / 8), mc = c % (BM / 8);
+            a_ok[q] = m0 + mc * 8 < g.M;
+            a_kk[q] = row;
+            a_off[q] = (uint32_t)(((kk_begin + row) * g.lda + m0 + mc * 8) * 2);
+            a_lds[q] = row * T::A_STRIDE + mc * 8;
+        }
+    }
+    if constexpr (BMODE == B_KCONTIG) {  // B stored [n][kk], tile BN x BK
+        b_step = BK * 2;
+#pragma unroll
+        for (int q = 0; q < T::B_CHUNKS; ++q) {
+            const int c = tid + T::THREADS * q, row = c / (BK / 8), kc = c % (BK / 8);
+            b_ok[q] = n0 + row < g.N;
+            b_kk[q] = kc * 8;
+            b_off[q] = (uint32_t)(((n0 + row) * g.ldb + kk_begin + kc * 8) * 2);
+            b_lds[q] = row * T::B_STRIDE + kc * 8;
+        }
+    } else {  // B stored [kk][n], tile BK x BN
+        b_step = (uint32_t)(BK * g.ldb * 2);
+#pragma unroll
+        for (int q = 0; q < T::B_CHUNKS; ++q) {
+            const int c = tid + T::THREADS * q, row = c / (BN / 8), nc = c % (BN / 8);
+            b_ok[q] = n0 + nc * 8 < g.N;
+            b_kk[q] = row;
+            b_off[q] = (uint32_t)(((kk_begin + row) * g.ldb + n0 + nc * 8) * 2);
+            b_lds[q] = row * T::B_STRIDE + nc * 8;
+        }
+    }
+    const int kk_len = (int)(kk_end - kk_begin);  // contraction elements of this slice (may be <= 0)
+
+    // D register sets hold the tiles in flight: tile t + D is requested while tile t is computed.
+    u32x4_t ra[D][T::A_CHUNKS > 0 ? T::A_CHUNKS : 1], rb[D][T::B_CHUNKS];
+
+    // Work-groups walk the contraction from different starting tiles (and wrap around): with a
+    // power-of-two row pitch all rows of a tile fall on the same one or two L2 channels, and the
+    // rotation spreads concurrently running work-groups over the channels.
+    const int stagger = num_tiles > 0 ? (int)(tile % num_tiles) : 0;
+    auto rotated = [&](int t) { return t + stagger - (t + stagger >= num_tiles ? num_tiles : 0); };
+
+    auto issue = [&](int set, int t_seq) {  // request the t_seq-th tile of this slice into register set `set`
+        const int t = t_seq < num_tiles ? rotated(t_seq) : t_seq;  // past the end: stays out of range, reads zeros
+        const int kk_tile = t * BK;
+        if constexpr (T::A_IN_LDS) {
 #pragma unroll
             for (int q = 0; q < T::A_CHUNKS; ++q) {
-                const int c = tid + T::THREADS * q, row = c / (BK / 8), kc = c % (BK / 8);
-                const int64_t gm = m0 + row, gk = kk0 + kc * 8;
-                ra[q] = ld16(g.A + gm * g.lda + gk, gm < g.M && gk < kk_end);
-            }
-        } else if constexpr (AMODE == A_MCONTIG) {  // A stored [kk][m], tile BK x BM
-#pragma unroll
-            for (int q = 0; q < T::A_CHUNKS; ++q) {
-                const int c = tid + T::THREADS * q, row = c / (BM / 8), mc = c % (BM / 8);
-                const int64_t gk = kk0 + row, gm = m0 + mc * 8;
-                ra[q] = ld16(g.A + gk * g.lda + gm, gk < kk_end && gm < g.M);
+                const bool ok = a_ok[q] && kk_tile + a_kk[q] < kk_len;
+                ra[set][q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, ok ? a_off[q] + (uint32_t)t * a_step : OOB,
+                                                                   0, 0);
             }
         }
-        if constexpr (BMODE == B_KCONTIG) {  // B stored [n][kk], tile BN x BK
 #pragma unroll
-            for (int q = 0; q < T::B_CHUNKS; ++q) {
-                const int c = tid + T::THREADS * q, row = c / (BK / 8), kc = c % (BK / 8);
-                const int64_t gn = n0 + row, gk = kk0 + kc * 8;
-                rb[q] = ld16(g.B + gn * g.ldb + gk, gn < g.N && gk < kk_end);
-            }
-        } else {  // B stored [kk][n], tile BK x BN
-#pragma unroll
-            for (int q = 0; q < T::B_CHUNKS; ++q) {
-                const int c = tid + T::THREADS * q, row = c / (BN / 8), nc = c % (BN / 8);
-                const int64_t gk = kk0 + row, gn = n0 + nc * 8;
-                rb[q] = ld16(g.B + gk * g.ldb + gn, gk < kk_end && gn < g.N);
-            }
+        for (int q = 0; q < T::B_CHUNKS; ++q) {
+            const bool ok = b_ok[q] && kk_tile + b_kk[q] < kk_len;
+            rb[set][q] =
+                __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, ok ? b_off[q] + (uint32_t)t * b_step : OOB, 0, 0);
         }
     };
 
-    auto store_lds = [&](int stage) {
+    auto store_lds = [&](int set, int stage) {
         bf16_t *As = lds + stage * T::STAGE_ELEMS;
         bf16_t *Bs = As + T::A_ELEMS;
-        if constexpr (AMODE == A_KCONTIG) {
+        if constexpr (T::A_IN_LDS) {
 #pragma unroll
-            for (int q = 0; q < T::A_CHUNKS; ++q) {
-                const int c = tid + T::THREADS * q, row = c / (BK / 8), kc = c % (BK / 8);
-                *reinterpret_cast<uint4 *>(As + row * T::A_STRIDE + kc * 8) = ra[q];
-            }
-        } else if constexpr (AMODE == A_MCONTIG) {
+            for (int q = 0; q < T::A_CHUNKS; ++q) *reinterpret_cast<u32x4_t *>(As + a_lds[q]) = ra[set][q];
+        }
 #pragma unroll
-            for (int q = 0; q < T::A_CHUNKS; ++q) {
-                const int c = tid + T::THREADS * q, row = c / (BM / 8), mc = c % (BM / 8);
-                *reinterpret_cast<uint4 *>(As + row * T::A_STRIDE + mc * 8) = ra[q];
+        for (int q = 0; q < T::B_CHUNKS; ++q) *reinterpret_cast<u32x4_t *>(Bs + b_lds[q]) = rb[set][q];
+    };
+
+    // Operand fragments of one 16-deep contraction step.
+    struct Frags {
+        bf16x8_t a[T::TM], b[T::TN];
+    };
+    constexpr int KS = BK / 16;  // contraction steps per tile
+
+    // Fragments of step `ks` of the tile whose data sits in LDS stage `stage` and whose first
+    // contraction index is kk0.  LDS reads (and the generator's ALU work) issued here run under
+    // the MFMAs of the step before.
+    Words4 rw[T::TM];  // Rademacher: the Philox words of the 128-token block the tile being fetched lies in
+    auto load_frags = [&](Frags &f, int stage, int64_t kk0, int ks) {
+        const bf16_t *As = lds + stage * T::STAGE_ELEMS;
+        const bf16_t *Bs = As + T::A_ELEMS;
+#pragma unroll
+        for (int a = 0; a < T::TM; ++a) {
+            const int row0 = wm * T::WTM + a * 32;
+            if constexpr (AMODE == A_KCONTIG) {
+                f.a[a] = frag_kcontig(As, T::A_STRIDE, row0, ks * 16, lane);
+            } else if constexpr (AMODE == A_MCONTIG) {
+                f.a[a] = frag_transposed(As, T::A_STRIDE, row0, ks * 16, lane);
+            } else {
+                const uint32_t j = (uint32_t)(m0 + row0 + (lane & 31));
+                const int64_t tok = kk0 + ks * 16 + ((lane >> 5) << 3);  // first of this lane's 8 tokens
+                if constexpr (AMODE == A_GAUSS) {
+                    f.a[a] = gauss_operand(g.st, (uint32_t)(tok >> 3), j);
+                } else {
+                    if (ks == 0)  // a tile (BK <= 128 tokens, aligned) never straddles two blocks
+                        rw[a] = philox4x32_10((uint32_t)(kk0 >> 7), j, g.st.off0, g.st.off1, g.st.key0, g.st.key1);
+                    f.a[a] = radem_operand(rw[a], (uint32_t)tok);
+                }
             }
         }
-        if constexpr (BMODE == B_KCONTIG) {
 #pragma unroll
-            for (int q = 0; q < T::B_CHUNKS; ++q) {
-                const int c = tid + T::THREADS * q, row = c / (BK / 8), kc = c % (BK / 8);
-                *reinterpret_cast<uint4 *>(Bs + row * T::B_STRIDE + kc * 8) = rb[q];
-            }
-        } else {
-#pragma unroll
-            for (int q = 0; q < T::B_CHUNKS; ++q) {
-                const int c = tid + T::THREADS * q, row = c / (BN / 8), nc = c % (BN / 8);
-                *reinterpret_cast<uint4 *>(Bs + row * T::B_STRIDE + nc * 8) = rb[q];
-            }
+        for (int b = 0; b < T::TN; ++b) {
+            const int col0 = wn * T::WTN + b * 32;
+            if constexpr (BMODE == B_KCONTIG)
+                f.b[b] = frag_kcontig(Bs, T::B_STRIDE, col0, ks * 16, lane);
+            else
+                f.b[b] = frag_transposed(Bs, T::B_STRIDE, col0, ks * 16, lane);
         }
     };
 
-    if (num_tiles > 0) {
-        load_global(kk_begin);
-        store_lds(0);
-    }
+    auto multiply = [&](const Frags &f) {
+#pragma unroll
+        for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+            for (int b = 0; b < T::TN; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[b], f.a[a], acc[a][b], 0, 0, 0);
+    };
+
+    // Pipeline.  Global side: tiles t+1 .. t+D-1 are in flight in D register sets while tile t is
+    // computed; the loop runs over whole groups of D tiles so that every load's register set is
+    // fixed at compile time, and tiles past the end read as zeros.  LDS side: two stages; the
+    // fragments of contraction step s+1 are fetched before the MFMAs of step s are issued, also
+    // across the tile boundary.  Per tile: after step 0, barrier (everyone is done reading the
+    // other stage), write tile t+1 there, and barrier again before its first fragments are read
+    // during the last step.
+#pragma unroll
+    for (int s = 0; s < D; ++s) issue(s, s);
+    store_lds(0, 0);
     __syncthreads();
-
-    for (int t = 0; t < num_tiles; ++t) {
-        const int64_t kk0 = kk_begin + (int64_t)t * BK;
-        const bool more = t + 1 < num_tiles;
-        if (more) load_global(kk0 + BK);
-
-        const bf16_t *As = lds + (t & 1) * T::STAGE_ELEMS;
-        const bf16_t *Bs = As + T::A_ELEMS;
-
-        Words4 rw[T::TM];
-        if constexpr (AMODE == A_RADEM) {
+    Frags cur, nxt;
+    load_frags(cur, 0, kk_begin + (int64_t)rotated(0) * BK, 0);
+    const int groups = (num_tiles + D - 1) / D;
+    for (int grp = 0; grp < groups; ++grp) {
 #pragma unroll
-            for (int a = 0; a < T::TM; ++a) {
-                const uint32_t j = (uint32_t)(m0 + wm * T::WTM + a * 32 + (lane & 31));
-                rw[a] = philox4x32_10((uint32_t)(kk0 >> 7), j, g.st.off0, g.st.off1, g.st.key0, g.st.key1);
-            }
-        }
-
+        for (int s = 0; s < D; ++s) {
+            const int t = grp * D + s;
+            const bool live = t < num_tiles;
+            const int64_t kk_t = kk_begin + (int64_t)(live ? rotated(t) : 0) * BK;
+            const int64_t kk_n = kk_begin + (int64_t)(t + 1 < num_tiles ? rotated(t + 1) : 0) * BK;
+#ifndef RMM_DEBUG_NOLOAD
+            issue(s, t + D);
+#endif
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8_t af[T::TM], bfr[T::TN];
-#pragma unroll
-            for (int a = 0; a < T::TM; ++a) {
-                const int row0 = wm * T::WTM + a * 32;
-                if constexpr (AMODE == A_KCONTIG) {
-                    af[a] = frag_kcontig(As, T::A_STRIDE, row0, ks * 16, lane);
-                } else if constexpr (AMODE == A_MCONTIG) {
-                    af[a] = frag_transposed(As, T::A_STRIDE, row0, ks * 16, lane);
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks == KS - 1) {
+                    if constexpr (KS > 1) __syncthreads();
+                    load_frags(nxt, (t + 1) & 1, kk_n, 0);
                 } else {
-                    const uint32_t j = (uint32_t)(m0 + row0 + (lane & 31));
-                    const int64_t tok = kk0 + ks * 16 + ((lane >> 5) << 3);  // first of this lane's 8 tokens
-                    if constexpr (AMODE == A_GAUSS)
-                        af[a] = gauss_operand(g.st, (uint32_t)(tok >> 3), j);
-                    else
-                        af[a] = radem_operand(rw[a], (uint32_t)tok);
+                    load_frags(nxt, t & 1, kk_t, ks + 1);
+                }
+                if (live) multiply(cur);
+                cur = nxt;
+                if (ks == 0) {
+                    __syncthreads();
+                    store_lds((s + 1) % D, (t + 1) & 1);
+                    if constexpr (KS == 1) __syncthreads();
                 }
             }
-#pragma unroll
-            for (int b = 0; b < T::TN; ++b) {
-                const int col0 = wn * T::WTN + b * 32;
-                if constexpr (BMODE == B_KCONTIG)
-                    bfr[b] = frag_kcontig(Bs, T::B_STRIDE, col0, ks * 16, lane);
-                else
-                    bfr[b] = frag_transposed(Bs, T::B_STRIDE, col0, ks * 16, lane);
-            }
-#pragma unroll
-            for (int a = 0; a < T::TM; ++a)
-#pragma unroll
-                for (int b = 0; b < T::TN; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
         }
-
-        if (more) store_lds((t + 1) & 1);
-        __syncthreads();
     }
 
-    // Epilogue.  Accumulator register v of lane l is C(8*(v/4) + 4*(l/32) + v%4, l%32) of its 32x32 tile.
+    // Epilogue.  The MFMA was issued with the operands swapped (B fragment first), so the
+    // accumulators hold C^T tiles: register v of lane l is C(l % 32, 8*(v/4) + 4*(l/32) + v%4)
+    // of its 32x32 tile, i.e. every lane owns four runs of four consecutive columns of one row.
 #pragma unroll
-    for (int a = 0; a < T::TM; ++a)
+    for (int a = 0; a < T::TM; ++a) {
+        const int64_t row = m0 + wm * T::WTM + a * 32 + (lane & 31);
+#ifdef RMM_DEBUG_NOEPI
+        if (row >= 0 && g.alpha != 123.0f) continue;
+#endif
+        if (row >= g.M) continue;
 #pragma unroll
-        for (int b = 0; b < T::TN; ++b) {
-            const int64_t col = n0 + wn * T::WTN + b * 32 + (lane & 31);
-            if (col >= g.N) continue;
-            float bias = 0.0f;
-            if constexpr (OUT == OUT_BF16)
-                if (g.bias != nullptr) bias = bf16_to_f32(g.bias[col]);
+        for (int b = 0; b < T::TN; ++b)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int64_t row = m0 + wm * T::WTM + a * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
-                if (row >= g.M) continue;
+            for (int q = 0; q < 4; ++q) {
+                const int64_t col = n0 + wn * T::WTN + b * 32 + 8 * q + 4 * (lane >> 5);
+                if (col >= g.N) continue;  // N is a multiple of 4, so a run is inside or outside as a whole
+                float r[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) r[u] = acc[a][b][4 * q + u];
                 if constexpr (OUT == OUT_BF16) {
-                    reinterpret_cast<bf16_t *>(g.C)[row * g.ldc + col] = f32_to_bf16(g.alpha * acc[a][b][v] + bias);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) r[u] *= g.alpha;
+                    if (g.bias != nullptr) {
+                        const uint2 bb = *reinterpret_cast<const uint2 *>(g.bias + col);
+                        r[0] += __uint_as_float(bb.x << 16);
+                        r[1] += __uint_as_float(bb.x & 0xFFFF0000u);
+                        r[2] += __uint_as_float(bb.y << 16);
+                        r[3] += __uint_as_float(bb.y & 0xFFFF0000u);
+                    }
+                    union {
+                        bf16x2_t h[2];
+                        uint2 u;
+                    } o;
+                    o.h[0] = __builtin_convertvector((f32x2_t){r[0], r[1]}, bf16x2_t);  // round to nearest even
+                    o.h[1] = __builtin_convertvector((f32x2_t){r[2], r[3]}, bf16x2_t);
+                    *reinterpret_cast<uint2 *>(reinterpret_cast<bf16_t *>(g.C) + row * g.ldc + col) = o.u;
                 } else {
-                    reinterpret_cast<float *>(g.C)[(int64_t)blockIdx.z * g.split_stride + row * g.ldc + col] =
-                        acc[a][b][v];
+                    *reinterpret_cast<float4 *>(reinterpret_cast<float *>(g.C) + (int64_t)blockIdx.z * g.split_stride +
+                                                row * g.ldc + col) = make_float4(r[0], r[1], r[2], r[3]);
                 }
             }
-        }
+    }
 }
 
 // out[r][c] (bf16) = alpha * sum_s part[s][r][c]; 8 columns per thread.
@@ -333,20 +427,59 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(const float *__res
     *reinterpret_cast<uint2 *>(out + e) = o;
 }
 
+// Prefetch depths (register sets of tiles in flight) to choose from.
+#ifndef RMM_TUNE_D1
+#define RMM_TUNE_D1 4
+#endif
+#ifndef RMM_TUNE_D2
+#define RMM_TUNE_D2 3
+#endif
+
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int AMODE, int BMODE, int OUT>
 hipError_t launch(const GemmArgs &g, int splits, hipStream_t stream) {
     const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     dim3 grid((unsigned)tiles, 1, (unsigned)splits);
-    gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, AMODE, BMODE, OUT><<<grid, 64 * WAVES_M * WAVES_N, 0, stream>>>(g);
+    // The kernel runs whole groups of D tiles; take the depth that wastes fewer.
+    const int64_t kt = (min(g.K, g.k_chunk) + BK - 1) / BK;
+    const int64_t pad1 = (kt + RMM_TUNE_D1 - 1) / RMM_TUNE_D1 * RMM_TUNE_D1 - kt;
+    const int64_t pad2 = (kt + RMM_TUNE_D2 - 1) / RMM_TUNE_D2 * RMM_TUNE_D2 - kt;
+    if (pad1 <= pad2)
+        gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, AMODE, BMODE, OUT, RMM_TUNE_D1>
+            <<<grid, 64 * WAVES_M * WAVES_N, 0, stream>>>(g);
+    else
+        gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, AMODE, BMODE, OUT, RMM_TUNE_D2>
+            <<<grid, 64 * WAVES_M * WAVES_N, 0, stream>>>(g);
     return hipGetLastError();
 }
 
 }  // namespace
 
+// Tile shapes: BM, BN, BK, waves along M, waves along N.
+#ifndef RMM_TUNE_NT
+#define RMM_TUNE_NT 128, 128, 64, 2, 2
+#endif
+#ifndef RMM_TUNE_NN
+#define RMM_TUNE_NN 128, 128, 64, 2, 2
+#endif
+#ifndef RMM_TUNE_DW
+#define RMM_TUNE_DW 128, 128, 64, 2, 2
+#endif
+#ifndef RMM_TUNE_SK
+#define RMM_TUNE_SK 128, 128, 64, 2, 2
+#endif
+#ifndef RMM_TUNE_SK_BM
+#define RMM_TUNE_SK_BM 128
+#define RMM_TUNE_SK_BN 128
+#endif
+#ifndef RMM_TUNE_SK_WGS
+#define RMM_TUNE_SK_WGS 512
+#endif
+
 bool mfma_shape_ok(int64_t n, int64_t d_in, int64_t d_out, int64_t k) {
-    (void)n;
-    (void)k;
-    return d_in % 8 == 0 && d_out % 8 == 0;
+    // 16-byte chunks need widths that are multiples of 8; buffer loads need operands below 2^31 bytes.
+    const int64_t lim = ((int64_t)1 << 31) / 2;
+    const int64_t rows = n > k ? n : k, cols = d_in > d_out ? d_in : d_out;
+    return d_in % 8 == 0 && d_out % 8 == 0 && rows * cols < lim && d_in * d_out < lim;
 }
 
 hipError_t launch_linear_nt_bf16(const bf16_t *X, const bf16_t *W, const bf16_t *bias, bf16_t *Y, int64_t n,
@@ -354,7 +487,8 @@ hipError_t launch_linear_nt_bf16(const bf16_t *X, const bf16_t *W, const bf16_t 
     GemmArgs g{};
     g.A = X, g.lda = d_in, g.B = W, g.ldb = d_in, g.C = Y, g.ldc = d_out, g.bias = bias;
     g.M = n, g.N = d_out, g.K = d_in, g.alpha = 1.0f, g.k_chunk = (d_in + 127) / 128 * 128;
-    return launch<128, 128, 64, 2, 2, A_KCONTIG, B_KCONTIG, OUT_BF16>(g, 1, stream);
+    g.a_bytes = n * d_in * 2, g.b_bytes = d_out * d_in * 2;
+    return launch<RMM_TUNE_NT, A_KCONTIG, B_KCONTIG, OUT_BF16>(g, 1, stream);
 }
 
 hipError_t launch_linear_nn_bf16(const bf16_t *dY, const bf16_t *W, bf16_t *dX, int64_t n, int64_t d_in,
@@ -362,7 +496,8 @@ hipError_t launch_linear_nn_bf16(const bf16_t *dY, const bf16_t *W, bf16_t *dX, 
     GemmArgs g{};
     g.A = dY, g.lda = d_out, g.B = W, g.ldb = d_in, g.C = dX, g.ldc = d_in, g.bias = nullptr;
     g.M = n, g.N = d_in, g.K = d_out, g.alpha = 1.0f, g.k_chunk = (d_out + 127) / 128 * 128;
-    return launch<128, 128, 64, 2, 2, A_KCONTIG, B_NCONTIG, OUT_BF16>(g, 1, stream);
+    g.a_bytes = n * d_out * 2, g.b_bytes = d_out * d_in * 2;
+    return launch<RMM_TUNE_NN, A_KCONTIG, B_NCONTIG, OUT_BF16>(g, 1, stream);
 }
 
 hipError_t launch_dw_bf16(const bf16_t *G, const bf16_t *X_proj, bf16_t *dW, int64_t k, int64_t d_in, int64_t d_out,
@@ -370,13 +505,14 @@ hipError_t launch_dw_bf16(const bf16_t *G, const bf16_t *X_proj, bf16_t *dW, int
     GemmArgs g{};
     g.A = G, g.lda = d_out, g.B = X_proj, g.ldb = d_in, g.C = dW, g.ldc = d_in, g.bias = nullptr;
     g.M = d_out, g.N = d_in, g.K = k, g.alpha = 1.0f, g.k_chunk = (k + 127) / 128 * 128;
-    return launch<128, 128, 64, 2, 2, A_MCONTIG, B_NCONTIG, OUT_BF16>(g, 1, stream);
+    g.a_bytes = k * d_out * 2, g.b_bytes = k * d_in * 2;
+    return launch<RMM_TUNE_DW, A_MCONTIG, B_NCONTIG, OUT_BF16>(g, 1, stream);
 }
 
 int sketch_splits_bf16(int64_t n, int64_t d, int64_t k) {
-    const int64_t tiles = ((k + 127) / 128) * ((d + 127) / 128);
+    const int64_t tiles = ((k + RMM_TUNE_SK_BM - 1) / RMM_TUNE_SK_BM) * ((d + RMM_TUNE_SK_BN - 1) / RMM_TUNE_SK_BN);
     const int64_t chunks = (n + 127) / 128;  // slices are multiples of 128 tokens
-    int64_t s = (2 * 256 + tiles - 1) / tiles;  // aim at two work-groups per compute unit
+    int64_t s = (RMM_TUNE_SK_WGS + tiles - 1) / tiles;  // work-groups aimed at
     if (s > chunks) s = chunks;
     if (s > 64) s = 64;
     if (s < 1) s = 1;
@@ -395,18 +531,19 @@ hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d
     GemmArgs g{};
     g.A = nullptr, g.lda = 0, g.B = A, g.ldb = d, g.bias = nullptr;
     g.M = k, g.N = d, g.K = n, g.st = st, g.ldc = d;
+    g.a_bytes = 0, g.b_bytes = n * d * 2;
     const int64_t chunks = (n + 127) / 128;
     g.k_chunk = (chunks + splits - 1) / splits * 128;
     hipError_t e;
     if (splits == 1) {
         g.C = out, g.alpha = alpha;
-        e = kind == 0 ? launch<128, 128, 64, 2, 2, A_GAUSS, B_NCONTIG, OUT_BF16>(g, 1, stream)
-                      : launch<128, 128, 64, 2, 2, A_RADEM, B_NCONTIG, OUT_BF16>(g, 1, stream);
+        e = kind == 0 ? launch<RMM_TUNE_SK, A_GAUSS, B_NCONTIG, OUT_BF16>(g, 1, stream)
+                      : launch<RMM_TUNE_SK, A_RADEM, B_NCONTIG, OUT_BF16>(g, 1, stream);
         return e;
     }
     g.C = ws, g.alpha = 1.0f, g.split_stride = k * d;
-    e = kind == 0 ? launch<128, 128, 64, 2, 2, A_GAUSS, B_NCONTIG, OUT_F32_PARTIAL>(g, splits, stream)
-                  : launch<128, 128, 64, 2, 2, A_RADEM, B_NCONTIG, OUT_F32_PARTIAL>(g, splits, stream);
+    e = kind == 0 ? launch<RMM_TUNE_SK, A_GAUSS, B_NCONTIG, OUT_F32_PARTIAL>(g, splits, stream)
+                  : launch<RMM_TUNE_SK, A_RADEM, B_NCONTIG, OUT_F32_PARTIAL>(g, splits, stream);
     if (e != hipSuccess) return e;
     const int64_t elems = k * d;  // d % 8 == 0, so elems % 4 == 0
     reduce_partials_kernel<<<(unsigned)((elems / 4 + 255) / 256), 256, 0, stream>>>((const float *)ws, out, elems,
