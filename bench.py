@@ -93,6 +93,8 @@ def main():
     ap.add_argument("--k", type=int, default=0, help="override the sketch size")
     ap.add_argument("--sets", type=int, default=4, help="rotating input/output sets (keeps the working set above the 256 MB last-level cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="only run a plain copy of this many MiB (counter calibration) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (no collective or sharded path exists)",
@@ -107,6 +109,16 @@ def main():
         print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
         return 2
     dev = torch.device("cuda:0")
+    if args.calibrate_copy:
+        # Plain device-to-device copy of a known size, for scaling the FETCH_SIZE / WRITE_SIZE counters.
+        nbytes = args.calibrate_copy << 20
+        src = torch.ones(nbytes, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": nbytes, "copy_bytes_written": nbytes, "copies": 5}))
+        return 0
     cfg = dict(synth.CONFIGS[args.workload])
     if args.k:
         cfg["k"] = args.k

@@ -434,6 +434,9 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(const float *__res
 #ifndef RMM_TUNE_D2
 #define RMM_TUNE_D2 3
 #endif
+#ifndef RMM_TUNE_SK_D
+#define RMM_TUNE_SK_D 2
+#endif
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int AMODE, int BMODE, int OUT>
 hipError_t launch(const GemmArgs &g, int splits, hipStream_t stream) {
@@ -441,6 +444,12 @@ hipError_t launch(const GemmArgs &g, int splits, hipStream_t stream) {
     dim3 grid((unsigned)tiles, 1, (unsigned)splits);
     // The kernel runs whole groups of D tiles; take the depth that wastes fewer.
     const int64_t kt = (min(g.K, g.k_chunk) + BK - 1) / BK;
+    if constexpr (AMODE == A_GAUSS || AMODE == A_RADEM) {
+        // The sketch kernels load one operand only and need their registers for wide wave tiles.
+        gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, AMODE, BMODE, OUT, RMM_TUNE_SK_D>
+            <<<grid, 64 * WAVES_M * WAVES_N, 0, stream>>>(g);
+        return hipGetLastError();
+    }
     const int64_t pad1 = (kt + RMM_TUNE_D1 - 1) / RMM_TUNE_D1 * RMM_TUNE_D1 - kt;
     const int64_t pad2 = (kt + RMM_TUNE_D2 - 1) / RMM_TUNE_D2 * RMM_TUNE_D2 - kt;
     if (pad1 <= pad2)
@@ -465,14 +474,14 @@ hipError_t launch(const GemmArgs &g, int splits, hipStream_t stream) {
 #define RMM_TUNE_DW 128, 128, 64, 2, 2
 #endif
 #ifndef RMM_TUNE_SK
-#define RMM_TUNE_SK 128, 128, 64, 2, 2
+#define RMM_TUNE_SK 128, 256, 64, 4, 1
 #endif
 #ifndef RMM_TUNE_SK_BM
 #define RMM_TUNE_SK_BM 128
-#define RMM_TUNE_SK_BN 128
+#define RMM_TUNE_SK_BN 256
 #endif
 #ifndef RMM_TUNE_SK_WGS
-#define RMM_TUNE_SK_WGS 512
+#define RMM_TUNE_SK_WGS 256
 #endif
 
 bool mfma_shape_ok(int64_t n, int64_t d_in, int64_t d_out, int64_t k) {
