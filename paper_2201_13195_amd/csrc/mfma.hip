@@ -366,44 +366,77 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_mfma_kernel(GemmA
     // Epilogue.  The MFMA was issued with the operands swapped (B fragment first), so the
     // accumulators hold C^T tiles: register v of lane l is C(l % 32, 8*(v/4) + 4*(l/32) + v%4)
     // of its 32x32 tile, i.e. every lane owns four runs of four consecutive columns of one row.
+    // Storing that directly would touch 32 rows with 16 bytes each per instruction; instead every
+    // wave passes a strip of 32 rows x 128 bytes through a private piece of LDS and writes it out
+    // with 16 bytes per lane, 8 lanes per row (full 128-byte lines).
+    __syncthreads();  // all fragment reads of the main loop are done; LDS is free
+    {
+        constexpr int EB = OUT == OUT_BF16 ? 2 : 4;         // bytes per output element
+        constexpr int CW = 128 / EB;                         // columns per strip: 64 (bf16) or 32 (fp32)
+        constexpr int TPS = CW / 32;                         // 32-column MFMA tiles per strip
+        constexpr int PITCH = 128 + 16;                      // bytes per strip row in LDS
+        static_assert(T::THREADS / 64 * 32 * PITCH <= T::LDS_BYTES, "staging area fits in LDS");
+        char *stage = reinterpret_cast<char *>(lds) + wave * 32 * PITCH;
+        const int r = lane & 31, h = lane >> 5;
 #pragma unroll
-    for (int a = 0; a < T::TM; ++a) {
-        const int64_t row = m0 + wm * T::WTM + a * 32 + (lane & 31);
-#ifdef RMM_DEBUG_NOEPI
-        if (row >= 0 && g.alpha != 123.0f) continue;
-#endif
-        if (row >= g.M) continue;
+        for (int a = 0; a < T::TM; ++a) {
+            const int64_t row0 = m0 + wm * T::WTM + a * 32;
 #pragma unroll
-        for (int b = 0; b < T::TN; ++b)
+            for (int b0 = 0; b0 < T::TN; b0 += TPS) {
+                const int64_t col0 = n0 + wn * T::WTN + b0 * 32;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int64_t col = n0 + wn * T::WTN + b * 32 + 8 * q + 4 * (lane >> 5);
-                if (col >= g.N) continue;  // N is a multiple of 4, so a run is inside or outside as a whole
-                float r[4];
+                for (int bb = 0; bb < TPS; ++bb) {
+                    if (b0 + bb >= T::TN) break;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) r[u] = acc[a][b][4 * q + u];
-                if constexpr (OUT == OUT_BF16) {
+                    for (int q = 0; q < 4; ++q) {
+                        float v[4];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) r[u] *= g.alpha;
-                    if (g.bias != nullptr) {
-                        const uint2 bb = *reinterpret_cast<const uint2 *>(g.bias + col);
-                        r[0] += __uint_as_float(bb.x << 16);
-                        r[1] += __uint_as_float(bb.x & 0xFFFF0000u);
-                        r[2] += __uint_as_float(bb.y << 16);
-                        r[3] += __uint_as_float(bb.y & 0xFFFF0000u);
+                        for (int u = 0; u < 4; ++u) v[u] = acc[a][b0 + bb][4 * q + u];
+                        const int c = bb * 32 + 8 * q + 4 * h;  // column inside the strip
+                        if constexpr (OUT == OUT_BF16) {
+#pragma unroll
+                            for (int u = 0; u < 4; ++u) v[u] *= g.alpha;
+                            if (g.bias != nullptr && col0 + c < g.N) {
+                                const uint2 bv = *reinterpret_cast<const uint2 *>(g.bias + col0 + c);
+                                v[0] += __uint_as_float(bv.x << 16);
+                                v[1] += __uint_as_float(bv.x & 0xFFFF0000u);
+                                v[2] += __uint_as_float(bv.y << 16);
+                                v[3] += __uint_as_float(bv.y & 0xFFFF0000u);
+                            }
+                            union {
+                                bf16x2_t hh[2];
+                                uint2 u;
+                            } o;
+                            o.hh[0] = __builtin_convertvector((f32x2_t){v[0], v[1]}, bf16x2_t);  // nearest even
+                            o.hh[1] = __builtin_convertvector((f32x2_t){v[2], v[3]}, bf16x2_t);
+                            *reinterpret_cast<uint2 *>(stage + r * PITCH + c * 2) = o.u;
+                        } else {
+                            *reinterpret_cast<float4 *>(stage + r * PITCH + c * 4) = make_float4(v[0], v[1], v[2], v[3]);
+                        }
                     }
-                    union {
-                        bf16x2_t h[2];
-                        uint2 u;
-                    } o;
-                    o.h[0] = __builtin_convertvector((f32x2_t){r[0], r[1]}, bf16x2_t);  // round to nearest even
-                    o.h[1] = __builtin_convertvector((f32x2_t){r[2], r[3]}, bf16x2_t);
-                    *reinterpret_cast<uint2 *>(reinterpret_cast<bf16_t *>(g.C) + row * g.ldc + col) = o.u;
-                } else {
-                    *reinterpret_cast<float4 *>(reinterpret_cast<float *>(g.C) + (int64_t)blockIdx.z * g.split_stride +
-                                                row * g.ldc + col) = make_float4(r[0], r[1], r[2], r[3]);
                 }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                // read back: lane l takes 16 bytes: chunk (l % 8) of row (l / 8) + 8*i
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int rr = (lane >> 3) + 8 * i, ch = lane & 7;
+                    const uint4 d = *reinterpret_cast<const uint4 *>(stage + rr * PITCH + ch * 16);
+                    const int64_t row = row0 + rr, col = col0 + ch * (16 / EB);
+#ifdef RMM_DEBUG_NOEPI
+                    if (g.alpha != 123.0f) continue;
+#endif
+                    if (row >= g.M || col >= g.N || ch * (16 / EB) >= (T::TN - b0) * 32) continue;
+                    if constexpr (OUT == OUT_BF16)
+                        *reinterpret_cast<uint4 *>(reinterpret_cast<bf16_t *>(g.C) + row * g.ldc + col) = d;
+                    else
+                        *reinterpret_cast<uint4 *>(reinterpret_cast<float *>(g.C) +
+                                                   (int64_t)blockIdx.z * g.split_stride + row * g.ldc + col) = d;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
             }
+        }
     }
 }
 
@@ -518,31 +551,33 @@ hipError_t launch_dw_bf16(const bf16_t *G, const bf16_t *X_proj, bf16_t *dW, int
     return launch<RMM_TUNE_DW, A_MCONTIG, B_NCONTIG, OUT_BF16>(g, 1, stream);
 }
 
-int sketch_splits_bf16(int64_t n, int64_t d, int64_t k) {
+// Token slices of the sketch product: at most one (tile, slice) pair per compute unit where
+// the tile count allows, each slice a multiple of 128 tokens, none empty.
+static int sketch_slices(int64_t n, int64_t d, int64_t k, int64_t *k_chunk) {
     const int64_t tiles = ((k + RMM_TUNE_SK_BM - 1) / RMM_TUNE_SK_BM) * ((d + RMM_TUNE_SK_BN - 1) / RMM_TUNE_SK_BN);
-    const int64_t chunks = (n + 127) / 128;  // slices are multiples of 128 tokens
-    int64_t s = (RMM_TUNE_SK_WGS + tiles - 1) / tiles;  // work-groups aimed at
-    if (s > chunks) s = chunks;
+    const int64_t blocks = (n + 127) / 128;
+    int64_t s = RMM_TUNE_SK_WGS / tiles;
+    if (s > blocks) s = blocks;
     if (s > 64) s = 64;
     if (s < 1) s = 1;
-    return (int)s;
+    *k_chunk = (blocks + s - 1) / s * 128;
+    return (int)((n + *k_chunk - 1) / *k_chunk);
 }
 
 size_t sketch_workspace_bf16(int64_t n, int64_t d, int64_t k) {
-    const int s = sketch_splits_bf16(n, d, k);
+    int64_t k_chunk;
+    const int s = sketch_slices(n, d, k, &k_chunk);
     return s > 1 ? (size_t)s * (size_t)k * (size_t)d * sizeof(float) : 0;
 }
 
 hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d, int64_t k, int kind, SketchState st,
                               void *ws, hipStream_t stream) {
-    const int splits = sketch_splits_bf16(n, d, k);
     const float alpha = 1.0f / sqrtf((float)k);
     GemmArgs g{};
     g.A = nullptr, g.lda = 0, g.B = A, g.ldb = d, g.bias = nullptr;
     g.M = k, g.N = d, g.K = n, g.st = st, g.ldc = d;
     g.a_bytes = 0, g.b_bytes = n * d * 2;
-    const int64_t chunks = (n + 127) / 128;
-    g.k_chunk = (chunks + splits - 1) / splits * 128;
+    const int splits = sketch_slices(n, d, k, &g.k_chunk);
     hipError_t e;
     if (splits == 1) {
         g.C = out, g.alpha = alpha;
