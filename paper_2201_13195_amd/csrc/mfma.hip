@@ -236,8 +236,13 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_mfma_kernel(GemmA
 
     // Work-groups walk the contraction from different starting tiles (and wrap around): with a
     // power-of-two row pitch all rows of a tile fall on the same one or two L2 channels, and the
-    // rotation spreads concurrently running work-groups over the channels.
-    const int stagger = num_tiles > 0 ? (int)(tile % num_tiles) : 0;
+    // rotation spreads concurrently running work-groups over the channels.  The eight tiles of one
+    // band column (same B column block, neighbouring A row blocks) share a starting tile so that
+    // their common operand is fetched once into L2.
+#ifndef RMM_STAGGER_DIV
+#define RMM_STAGGER_DIV 8
+#endif
+    const int stagger = (num_tiles > 0 && RMM_STAGGER_DIV > 0) ? (int)((tile / RMM_STAGGER_DIV) % num_tiles) : 0;
     auto rotated = [&](int t) { return t + stagger - (t + stagger >= num_tiles ? num_tiles : 0); };
 
     auto issue = [&](int set, int t_seq) {  // request the t_seq-th tile of this slice into register set `set`
