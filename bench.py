@@ -83,6 +83,30 @@ def cpu_baseline(cfg, kind, budget_s=10.0):
             "ms_per_step": dt / reps * 1e3}
 
 
+def sketch_roofline(torch, rmm, binding, dev, kind, kind_name, n=16384, d=4096, k=32, reps=30):
+    """rmm_sketch (S^T A) at small k on a RoBERTa-large sized operand: bound by one read of A.
+    Three operands are rotated (402 MB) so that no call finds its input in the last-level cache.
+    The time is that of the whole call (streaming kernel + the small partial-sum kernel)."""
+    bufs = [torch.randn((n, d), device=dev).bfloat16() for _ in range(3)]
+    out = torch.empty((k, d), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(max(rmm.rmm_workspace_bytes(n, d, d, k, torch.bfloat16, kind, binding.OP_SKETCH), 16),
+                     dtype=torch.uint8, device=dev)
+    for i in range(3):
+        rmm.rmm_sketch(bufs[i], k, kind, 1, i, out=out, ws=ws)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for i in range(reps):
+        evs[i][0].record()
+        rmm.rmm_sketch(bufs[i % 3], k, kind, 1, i, out=out, ws=ws)
+        evs[i][1].record()
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in evs)[reps // 2]
+    nbytes = 2 * (n * d + k * d)
+    return {"workload": "rmm_sketch N=%d d=%d k=%d (%s), bf16" % (n, d, k, kind_name), "bound": "hbm",
+            "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "avg_call_ms": ms, "algorithmic_bytes_per_call": nbytes}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -93,6 +117,8 @@ def main():
     ap.add_argument("--k", type=int, default=0, help="override the sketch size")
     ap.add_argument("--sets", type=int, default=4, help="rotating input/output sets (keeps the working set above the 256 MB last-level cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sketch-roofline", action="store_true",
+                    help="skip the small-k rmm_sketch measurement against the HBM roofline")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="only run a plain copy of this many MiB (counter calibration) and exit")
     args = ap.parse_args()
@@ -209,6 +235,8 @@ def main():
         "stages_ms": stage_ms,
         "stages_tflops": {s: fl[s] / (stage_ms[s] * 1e-3) / 1e12 for s in STAGES},
     }
+    if not args.no_sketch_roofline:
+        out["sketch_hbm_roofline"] = sketch_roofline(torch, rmm, binding, dev, kind, args.kind)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, kind)
     print(json.dumps(out))

@@ -465,6 +465,158 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(const float *__res
     *reinterpret_cast<uint2 *>(out + e) = o;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Small sketch sizes (k <= 64): S^T A is bound by reading A once from HBM, so this kernel is a
+// streaming pass.  A work-group owns 256 columns and one slice of tokens and walks the slice 64
+// tokens at a time (global -> registers, D steps in flight -> LDS, two stages).  The four waves
+// split the contraction: wave w takes tokens 16w .. 16w+15 of every step, for all 32*TM sketch
+// columns and all 256 operand columns, so every sketch entry is generated exactly once per
+// work-group and the generator's ALU work stays far below the memory time.  At the end the four
+// partial accumulators are summed through LDS and written as fp32 partials of the slice (or,
+// with a single slice, scaled and rounded to bf16).
+struct SmallkArgs {
+    const bf16_t *A;  // n x d
+    void *C;          // bf16 k x d, or fp32 partials [slice][k][d]
+    int64_t n, d, k;
+    int64_t a_bytes;
+    int64_t k_chunk;  // tokens per slice (multiple of 128)
+    float alpha;
+    SketchState st;
+};
+
+template <int TM, int KIND, int D, int OUT>
+__global__ void __launch_bounds__(256) sketch_smallk_kernel(SmallkArgs g) {
+    constexpr int BN = 256, BK = 64, STRIDE = BN + TPAD, STAGE_ELEMS = BK * STRIDE, CHUNKS = BN * BK / 8 / 256;
+    constexpr int TN = BN / 32;
+    __shared__ __attribute__((aligned(16))) bf16_t lds[2 * STAGE_ELEMS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t n0 = (int64_t)blockIdx.x * BN;
+    const int64_t kk_begin = (int64_t)blockIdx.y * g.k_chunk;
+    const int kk_len = (int)(min(g.n, kk_begin + g.k_chunk) - kk_begin);  // >= 1: the host makes no empty slice
+    const int num_tiles = (kk_len + BK - 1) / BK;
+
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(g.A), (short)0, (int)g.a_bytes, 0x00020000);
+    constexpr uint32_t OOB = 0x80000000u;
+    uint32_t off[CHUNKS];
+    int row_of[CHUNKS], lds_of[CHUNKS];
+#pragma unroll
+    for (int q = 0; q < CHUNKS; ++q) {
+        const int c = tid + 256 * q, row = c / (BN / 8), nc = c % (BN / 8);
+        row_of[q] = row, lds_of[q] = row * STRIDE + nc * 8;
+        off[q] = n0 + nc * 8 < g.d ? (uint32_t)(((kk_begin + row) * g.d + n0 + nc * 8) * 2) : OOB;
+    }
+    const uint32_t step_bytes = (uint32_t)(BK * g.d * 2);
+
+    u32x4_t rb[D][CHUNKS];
+    auto issue = [&](int set, int t) {
+#pragma unroll
+        for (int q = 0; q < CHUNKS; ++q) {
+            const bool ok = t * BK + row_of[q] < kk_len;  // also false for every t >= num_tiles
+            rb[set][q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, ok ? off[q] + (uint32_t)t * step_bytes : OOB, 0, 0);
+        }
+    };
+    auto store_lds = [&](int set, int stage) {
+#pragma unroll
+        for (int q = 0; q < CHUNKS; ++q)
+            *reinterpret_cast<u32x4_t *>(lds + stage * STAGE_ELEMS + lds_of[q]) = rb[set][q];
+    };
+
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+
+#pragma unroll
+    for (int s = 0; s < D; ++s) issue(s, s);
+    store_lds(0, 0);
+    __syncthreads();
+    const int groups = (num_tiles + D - 1) / D;
+    for (int grp = 0; grp < groups; ++grp) {
+#pragma unroll
+        for (int s = 0; s < D; ++s) {
+            const int t = grp * D + s;
+            issue(s, t + D);
+            if (t < num_tiles) {
+                const bf16_t *Bs = lds + (t & 1) * STAGE_ELEMS;
+                const int tok = (int)kk_begin + t * BK + 16 * wave + ((lane >> 5) << 3);  // this lane's first token
+                bf16x8_t af[TM], bfr[TN];
+#pragma unroll
+                for (int a = 0; a < TM; ++a) {
+                    const uint32_t j = (uint32_t)(a * 32 + (lane & 31));
+                    if constexpr (KIND == 0) {
+                        af[a] = gauss_operand(g.st, (uint32_t)(tok >> 3), j);
+                    } else {
+                        const Words4 rw =
+                            philox4x32_10((uint32_t)(tok >> 7), j, g.st.off0, g.st.off1, g.st.key0, g.st.key1);
+                        af[a] = radem_operand(rw, (uint32_t)tok);
+                    }
+                }
+#pragma unroll
+                for (int b = 0; b < TN; ++b) bfr[b] = frag_transposed(Bs, STRIDE, b * 32, 16 * wave, lane);
+#pragma unroll
+                for (int a = 0; a < TM; ++a)
+#pragma unroll
+                    for (int b = 0; b < TN; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[b], af[a], acc[a][b], 0, 0, 0);
+            }
+            store_lds((s + 1) % D, (t + 1) & 1);
+            __syncthreads();  // step t is consumed everywhere, step t+1 is visible
+        }
+    }
+
+    // Sum the four waves' accumulators, 32 rows x 128 columns at a time: every wave puts its block
+    // into its own LDS region, then all threads add the four regions and write full rows.
+    // (Accumulator register v of lane l is C(l % 32, 8*(v/4) + 4*(l/32) + v%4) of a 32x32 tile.)
+    constexpr int PITCH = 128 * 4 + 16;  // bytes per row of a region
+    static_assert(4 * 32 * PITCH <= 2 * STAGE_ELEMS * 2, "reduction regions fit in LDS");
+    char *region = reinterpret_cast<char *>(lds);
+    const int r = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+#pragma unroll
+            for (int bb = 0; bb < 4; ++bb)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x16_t &t = acc[a][half * 4 + bb];
+                    *reinterpret_cast<float4 *>(region + (wave * 32 + r) * PITCH + (bb * 32 + 8 * q + 4 * h) * 4) =
+                        make_float4(t[4 * q], t[4 * q + 1], t[4 * q + 2], t[4 * q + 3]);
+                }
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int f = tid + 256 * i, row = f >> 5, c4 = f & 31;
+                float4 s = *reinterpret_cast<const float4 *>(region + row * PITCH + c4 * 16);
+#pragma unroll
+                for (int w = 1; w < 4; ++w) {
+                    const float4 p = *reinterpret_cast<const float4 *>(region + (w * 32 + row) * PITCH + c4 * 16);
+                    s.x += p.x, s.y += p.y, s.z += p.z, s.w += p.w;
+                }
+                const int64_t grow = a * 32 + row, gcol = n0 + half * 128 + c4 * 4;
+                if (grow < g.k && gcol < g.d) {  // d is a multiple of 4
+                    if constexpr (OUT == OUT_BF16) {
+                        union {
+                            bf16x2_t hh[2];
+                            uint2 u;
+                        } o;
+                        o.hh[0] = __builtin_convertvector((f32x2_t){g.alpha * s.x, g.alpha * s.y}, bf16x2_t);
+                        o.hh[1] = __builtin_convertvector((f32x2_t){g.alpha * s.z, g.alpha * s.w}, bf16x2_t);
+                        *reinterpret_cast<uint2 *>(reinterpret_cast<bf16_t *>(g.C) + grow * g.d + gcol) = o.u;
+                    } else {
+                        *reinterpret_cast<float4 *>(reinterpret_cast<float *>(g.C) +
+                                                    ((int64_t)blockIdx.y * g.k + grow) * g.d + gcol) = s;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+}
+
 // Prefetch depths (register sets of tiles in flight) to choose from.
 #ifndef RMM_TUNE_D1
 #define RMM_TUNE_D1 4
@@ -521,6 +673,16 @@ hipError_t launch(const GemmArgs &g, int splits, hipStream_t stream) {
 #ifndef RMM_TUNE_SK_WGS
 #define RMM_TUNE_SK_WGS 256
 #endif
+// Streaming kernel for k <= 64: work-groups aimed at, prefetch depth for k <= 32 and for k <= 64.
+#ifndef RMM_TUNE_SMALLK_WGS
+#define RMM_TUNE_SMALLK_WGS 256
+#endif
+#ifndef RMM_TUNE_SMALLK_D1
+#define RMM_TUNE_SMALLK_D1 4
+#endif
+#ifndef RMM_TUNE_SMALLK_D2
+#define RMM_TUNE_SMALLK_D2 4
+#endif
 
 bool mfma_shape_ok(int64_t n, int64_t d_in, int64_t d_out, int64_t k) {
     // 16-byte chunks need widths that are multiples of 8; buffer loads need operands below 2^31 bytes.
@@ -569,15 +731,50 @@ static int sketch_slices(int64_t n, int64_t d, int64_t k, int64_t *k_chunk) {
     return (int)((n + *k_chunk - 1) / *k_chunk);
 }
 
+// Same for the streaming kernel of small sketch sizes (256-column work-groups, one per compute unit).
+constexpr int64_t kSmallK = 64;
+static int smallk_slices(int64_t n, int64_t d, int64_t *k_chunk) {
+    const int64_t col_tiles = (d + 255) / 256, blocks = (n + 127) / 128;
+    int64_t s = RMM_TUNE_SMALLK_WGS / col_tiles;
+    if (s > blocks) s = blocks;
+    if (s < 1) s = 1;
+    *k_chunk = (blocks + s - 1) / s * 128;
+    return (int)((n + *k_chunk - 1) / *k_chunk);
+}
+
 size_t sketch_workspace_bf16(int64_t n, int64_t d, int64_t k) {
     int64_t k_chunk;
-    const int s = sketch_slices(n, d, k, &k_chunk);
+    const int s = k <= kSmallK ? smallk_slices(n, d, &k_chunk) : sketch_slices(n, d, k, &k_chunk);
     return s > 1 ? (size_t)s * (size_t)k * (size_t)d * sizeof(float) : 0;
+}
+
+template <int TM, int KIND>
+static hipError_t launch_smallk(const SmallkArgs &g, int slices, hipStream_t stream) {
+    constexpr int D = TM == 1 ? RMM_TUNE_SMALLK_D1 : RMM_TUNE_SMALLK_D2;
+    dim3 grid((unsigned)((g.d + 255) / 256), (unsigned)slices);
+    if (slices == 1)
+        sketch_smallk_kernel<TM, KIND, D, OUT_BF16><<<grid, 256, 0, stream>>>(g);
+    else
+        sketch_smallk_kernel<TM, KIND, D, OUT_F32_PARTIAL><<<grid, 256, 0, stream>>>(g);
+    return hipGetLastError();
 }
 
 hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d, int64_t k, int kind, SketchState st,
                               void *ws, hipStream_t stream) {
     const float alpha = 1.0f / sqrtf((float)k);
+    if (k <= kSmallK) {  // bound by one pass over A: streaming kernel
+        SmallkArgs a{};
+        a.A = A, a.n = n, a.d = d, a.k = k, a.a_bytes = n * d * 2, a.st = st;
+        const int slices = smallk_slices(n, d, &a.k_chunk);
+        a.C = slices == 1 ? (void *)out : ws, a.alpha = alpha;
+        hipError_t e = k <= 32 ? (kind == 0 ? launch_smallk<1, 0>(a, slices, stream) : launch_smallk<1, 1>(a, slices, stream))
+                               : (kind == 0 ? launch_smallk<2, 0>(a, slices, stream) : launch_smallk<2, 1>(a, slices, stream));
+        if (e != hipSuccess || slices == 1) return e;
+        const int64_t elems = k * d;
+        reduce_partials_kernel<<<(unsigned)((elems / 4 + 255) / 256), 256, 0, stream>>>((const float *)ws, out, elems,
+                                                                                         slices, k * d, alpha);
+        return hipGetLastError();
+    }
     GemmArgs g{};
     g.A = nullptr, g.lda = 0, g.B = A, g.ldb = d, g.bias = nullptr;
     g.M = k, g.N = d, g.K = n, g.st = st, g.ldc = d;

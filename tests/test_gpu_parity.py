@@ -137,6 +137,29 @@ def test_config4_large(name, offset):
     check_layer(X, W, dY, c["k"], rmm.GAUSSIAN, c["seed"], offset, "bf16", label=name)
 
 
+@pytest.mark.parametrize("kind", [rmm.GAUSSIAN, rmm.RADEMACHER])
+@pytest.mark.parametrize("n,d,k", [(4100, 520, 24), (4100, 520, 64), (700, 264, 33), (16384, 4096, 32)])
+def test_sketch_primitive_small_k(n, d, k, kind):
+    """rmm_sketch alone (Eq. 4) in the regime bound by one pass over A (k <= 64), several token
+    slices, ragged tails; the last case is the shape the HBM roofline is quoted on."""
+    A = synth.to_torch(synth.normal((n, d), 31), "bf16")
+    got = rmm.rmm_sketch(A.to(DEV), k, kind, 0x5EED0006, 9)
+    torch.cuda.synchronize()
+    want = o_rmm.sketch_apply(synth.to_f64(A), k, kind, 0x5EED0006, 9)
+    err = rel_fro(got, want)
+    print("sketch n=%d d=%d k=%d kind=%d: %.2e" % (n, d, k, kind, err), flush=True)
+    assert err <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("kind", [rmm.GAUSSIAN, rmm.RADEMACHER])
+def test_sketch_primitive_large_k(kind):
+    A = synth.to_torch(synth.normal((3000, 392), 32), "bf16")
+    got = rmm.rmm_sketch(A.to(DEV), 300, kind, 0x5EED0007, 2)
+    torch.cuda.synchronize()
+    want = o_rmm.sketch_apply(synth.to_f64(A), 300, kind, 0x5EED0007, 2)
+    assert rel_fro(got, want) <= TOL["bf16"]
+
+
 # ----------------------------------------------------------------------------- contracts of the boundary
 
 def test_forward_and_sketch_agree_and_are_deterministic():
