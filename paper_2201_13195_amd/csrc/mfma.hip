@@ -54,6 +54,9 @@ struct GemmArgs {
     SketchState st;
     int64_t k_chunk;       // contraction elements per blockIdx.z slice (multiple of 128)
     int64_t split_stride;  // fp32 elements between the partial results of two slices
+#ifdef RMM_DEBUG_TRACE
+    unsigned long long *trace;
+#endif
 };
 
 // Eight unscaled Gaussian entries P[8*c0 .. 8*c0+7][j] as a bf16 MFMA operand.
@@ -91,9 +94,9 @@ __device__ __forceinline__ bf16x8_t radem_operand(const Words4 &r, uint32_t t0) 
     return out.v;
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int AMODE, int BMODE, int OUT>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int WAVES_K, int AMODE, int BMODE, int OUT>
 struct Tile {
-    static constexpr int THREADS = 64 * WAVES_M * WAVES_N;
+    static constexpr int THREADS = 64 * WAVES_M * WAVES_N * WAVES_K;  // WAVES_K groups of waves split the contraction
     static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // wave tile
     static constexpr int TM = WTM / 32, TN = WTN / 32;            // 32x32 MFMA tiles per wave
     static constexpr bool A_IN_LDS = (AMODE == A_KCONTIG || AMODE == A_MCONTIG);
@@ -104,10 +107,11 @@ struct Tile {
     static constexpr int A_ELEMS = A_IN_LDS ? A_ROWS * A_STRIDE : 0;
     static constexpr int B_ELEMS = B_ROWS * B_STRIDE;
     static constexpr int STAGE_ELEMS = A_ELEMS + B_ELEMS;
-    static constexpr int LDS_BYTES = 2 * STAGE_ELEMS * 2;
+    static constexpr int STAGES = 3;  // LDS stages: tile t is computed while tile t+2 is written
+    static constexpr int LDS_BYTES = STAGES * STAGE_ELEMS * 2;
     static constexpr int A_CHUNKS = A_IN_LDS ? BM * BK / 8 / THREADS : 0;  // 16-byte chunks per thread and tile
     static constexpr int B_CHUNKS = BN * BK / 8 / THREADS;
-    static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0 && BK % 16 == 0, "tile shape");
+    static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0 && BK % (16 * WAVES_K) == 0, "tile shape");
     static_assert((BM * BK / 8) % THREADS == 0 && (BN * BK / 8) % THREADS == 0, "chunks per thread");
 };
 
@@ -137,13 +141,16 @@ __device__ __forceinline__ bf16x8_t frag_transposed(const bf16_t *tile, int stri
     return out.v;
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int AMODE, int BMODE, int OUT, int D>
-__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_mfma_kernel(GemmArgs g) {
-    typedef Tile<BM, BN, BK, WAVES_M, WAVES_N, AMODE, BMODE, OUT> T;
-    __shared__ __attribute__((aligned(16))) bf16_t lds[2 * T::STAGE_ELEMS];
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int WAVES_K, int AMODE, int BMODE, int OUT, int D>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) gemm_mfma_kernel(GemmArgs g) {
+    typedef Tile<BM, BN, BK, WAVES_M, WAVES_N, WAVES_K, AMODE, BMODE, OUT> T;
+    __shared__ __attribute__((aligned(16))) bf16_t lds[T::STAGES * T::STAGE_ELEMS];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    // Wave w works on the (wm, wn) part of the tile and, of every 16-deep contraction step s,
+    // on those with s % WAVES_K == kg.
+    const int kg = wave / (WAVES_M * WAVES_N), wmn = wave % (WAVES_M * WAVES_N);
+    const int wm = wmn / WAVES_N, wn = wmn % WAVES_N;
     // Tile order.  Work-groups are dealt round-robin to the 8 XCDs (each with its own L2), so first
     // renumber them such that one XCD owns a contiguous run of positions; then walk the tile grid
     // in bands of GROUP_M tile rows, column by column, so that the work-groups resident on one XCD
@@ -279,13 +286,15 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_mfma_kernel(GemmA
     struct Frags {
         bf16x8_t a[T::TM], b[T::TN];
     };
-    constexpr int KS = BK / 16;  // contraction steps per tile
+    constexpr int KS = BK / 16 / WAVES_K;  // 16-deep contraction steps per tile and wave: kg, kg + WAVES_K, ...
+    static_assert(KS >= 2, "the pipeline needs two contraction steps per tile and wave");
 
     // Fragments of step `ks` of the tile whose data sits in LDS stage `stage` and whose first
     // contraction index is kk0.  LDS reads (and the generator's ALU work) issued here run under
     // the MFMAs of the step before.
     Words4 rw[T::TM];  // Rademacher: the Philox words of the 128-token block the tile being fetched lies in
-    auto load_frags = [&](Frags &f, int stage, int64_t kk0, int ks) {
+    auto load_frags = [&](Frags &f, int stage, int64_t kk0, int ks_local) {
+        const int ks = ks_local * WAVES_K + kg;  // this wave's ks_local-th step of the tile
         const bf16_t *As = lds + stage * T::STAGE_ELEMS;
         const bf16_t *Bs = As + T::A_ELEMS;
 #pragma unroll
@@ -301,7 +310,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_mfma_kernel(GemmA
                 if constexpr (AMODE == A_GAUSS) {
                     f.a[a] = gauss_operand(g.st, (uint32_t)(tok >> 3), j);
                 } else {
-                    if (ks == 0)  // a tile (BK <= 128 tokens, aligned) never straddles two blocks
+                    if (ks_local == 0)  // a tile (BK <= 128 tokens, aligned) never straddles two blocks
                         rw[a] = philox4x32_10((uint32_t)(kk0 >> 7), j, g.st.off0, g.st.off1, g.st.key0, g.st.key1);
                     f.a[a] = radem_operand(rw[a], (uint32_t)tok);
                 }
@@ -325,48 +334,62 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_mfma_kernel(GemmA
                 acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[b], f.a[a], acc[a][b], 0, 0, 0);
     };
 
-    // Pipeline.  Global side: tiles t+1 .. t+D-1 are in flight in D register sets while tile t is
-    // computed; the loop runs over whole groups of D tiles so that every load's register set is
-    // fixed at compile time, and tiles past the end read as zeros.  LDS side: two stages; the
-    // fragments of contraction step s+1 are fetched before the MFMAs of step s are issued, also
-    // across the tile boundary.  Per tile: after step 0, barrier (everyone is done reading the
-    // other stage), write tile t+1 there, and barrier again before its first fragments are read
-    // during the last step.
+    // Pipeline.  Global side: tiles t+3 .. t+D-1 are in flight in D register sets (tile u in set
+    // u % D) while tile t is computed; the loop runs over whole groups of D tiles so that every
+    // load's register set is fixed at compile time, and tiles past the end read as zeros.  LDS side:
+    // three stages (tile u in stage u % 3).  During step t tile t+2 is written: its stage was last
+    // read in step t-1, which every wave has left, and it is first read at the end of step t+1,
+    // after the barrier that closes step t+1 ... so ONE barrier per step is enough, and the
+    // fragments of the next 16-deep contraction step are always fetched before the MFMAs of the
+    // current one are issued, also across the tile boundary.
+    static_assert(D >= 3, "tile t+2 must have been requested before step t");
+#ifdef RMM_DEBUG_TRACE
+    unsigned long long *tr = g.trace ? g.trace + ((size_t)blockIdx.x + (size_t)gridDim.x * blockIdx.z) * 64 : nullptr;
+    if (tr && tid == 0) tr[0] = clock64(), tr[62] = wall_clock64();
+#endif
 #pragma unroll
     for (int s = 0; s < D; ++s) issue(s, s);
     store_lds(0, 0);
+    store_lds(1, 1);
     __syncthreads();
     Frags cur, nxt;
     load_frags(cur, 0, kk_begin + (int64_t)rotated(0) * BK, 0);
     const int groups = (num_tiles + D - 1) / D;
+    int st_cur = 0;  // stage of tile t
+#ifdef RMM_DEBUG_TRACE
+    if (tr && tid == 0) tr[1] = clock64();
+#endif
     for (int grp = 0; grp < groups; ++grp) {
 #pragma unroll
         for (int s = 0; s < D; ++s) {
             const int t = grp * D + s;
-            const bool live = t < num_tiles;
-            const int64_t kk_t = kk_begin + (int64_t)(live ? rotated(t) : 0) * BK;
+            const int64_t kk_t = kk_begin + (int64_t)(t < num_tiles ? rotated(t) : 0) * BK;
             const int64_t kk_n = kk_begin + (int64_t)(t + 1 < num_tiles ? rotated(t + 1) : 0) * BK;
+            const int st_next = st_cur == 2 ? 0 : st_cur + 1, st_write = st_next == 2 ? 0 : st_next + 1;
 #ifndef RMM_DEBUG_NOLOAD
             issue(s, t + D);
 #endif
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                if (ks == KS - 1) {
-                    if constexpr (KS > 1) __syncthreads();
-                    load_frags(nxt, (t + 1) & 1, kk_n, 0);
-                } else {
-                    load_frags(nxt, t & 1, kk_t, ks + 1);
-                }
-                if (live) multiply(cur);
+                if (ks == KS - 1)
+                    load_frags(nxt, st_next, kk_n, 0);
+                else
+                    load_frags(nxt, st_cur, kk_t, ks + 1);
+                multiply(cur);  // tiles past the end are all zeros: no branch, the step stays one basic block
                 cur = nxt;
-                if (ks == 0) {
-                    __syncthreads();
-                    store_lds((s + 1) % D, (t + 1) & 1);
-                    if constexpr (KS == 1) __syncthreads();
-                }
+                if (ks == 0) store_lds((s + 2) % D, st_write);
             }
+            __builtin_amdgcn_iglp_opt(0);  // ask the scheduler to interleave LDS / global traffic with the MFMAs
+            __syncthreads();
+            st_cur = st_next;
+#ifdef RMM_DEBUG_TRACE
+            if (tr && tid == 0 && t + 2 < 60) tr[t + 2] = clock64();
+#endif
         }
     }
+#ifdef RMM_DEBUG_TRACE
+    if (tr && tid == 0) tr[60] = clock64();
+#endif
 
     // Epilogue.  The MFMA was issued with the operands swapped (B fragment first), so the
     // accumulators hold C^T tiles: register v of lane l is C(l % 32, 8*(v/4) + 4*(l/32) + v%4)
@@ -375,7 +398,42 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_mfma_kernel(GemmA
     // wave passes a strip of 32 rows x 128 bytes through a private piece of LDS and writes it out
     // with 16 bytes per lane, 8 lanes per row (full 128-byte lines).
     __syncthreads();  // all fragment reads of the main loop are done; LDS is free
-    {
+    if constexpr (WAVES_K > 1) {
+        // Sum the accumulators of the WAVES_K wave groups into group 0: the other groups park theirs
+        // in LDS, 16 bytes per lane and run, laid out so that consecutive lanes are consecutive.
+        constexpr int GROUP_THREADS = 64 * WAVES_M * WAVES_N;
+        constexpr int RUNS = T::TM * T::TN * 4;
+        static_assert((WAVES_K - 1) * RUNS * GROUP_THREADS * 16 <= T::LDS_BYTES, "accumulators of the other groups fit in LDS");
+        float4 *park = reinterpret_cast<float4 *>(lds);
+        const int tg = tid % GROUP_THREADS;
+        if (kg > 0) {
+#pragma unroll
+            for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+                for (int b = 0; b < T::TN; ++b)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        park[((kg - 1) * RUNS + (a * T::TN + b) * 4 + q) * GROUP_THREADS + tg] =
+                            make_float4(acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
+        }
+        __syncthreads();
+        if (kg == 0) {
+#pragma unroll
+            for (int o = 1; o < WAVES_K; ++o)
+#pragma unroll
+                for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+                    for (int b = 0; b < T::TN; ++b)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const float4 p = park[((o - 1) * RUNS + (a * T::TN + b) * 4 + q) * GROUP_THREADS + tg];
+                            acc[a][b][4 * q] += p.x, acc[a][b][4 * q + 1] += p.y;
+                            acc[a][b][4 * q + 2] += p.z, acc[a][b][4 * q + 3] += p.w;
+                        }
+        }
+        __syncthreads();
+    }
+    if (kg == 0) {
         constexpr int EB = OUT == OUT_BF16 ? 2 : 4;         // bytes per output element
         constexpr int CW = 128 / EB;                         // columns per strip: 64 (bf16) or 32 (fp32)
         constexpr int TPS = CW / 32;                         // 32-column MFMA tiles per strip
@@ -443,6 +501,9 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_mfma_kernel(GemmA
             }
         }
     }
+#ifdef RMM_DEBUG_TRACE
+    if (tr && tid == 0) tr[63] = clock64(), tr[61] = wall_clock64();
+#endif
 }
 
 // out[r][c] (bf16) = alpha * sum_s part[s][r][c]; 8 columns per thread.
@@ -625,46 +686,72 @@ __global__ void __launch_bounds__(256) sketch_smallk_kernel(SmallkArgs g) {
 #define RMM_TUNE_D2 3
 #endif
 #ifndef RMM_TUNE_SK_D
-#define RMM_TUNE_SK_D 2
+#define RMM_TUNE_SK_D 3
 #endif
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int AMODE, int BMODE, int OUT>
-hipError_t launch(const GemmArgs &g, int splits, hipStream_t stream) {
+#ifdef RMM_DEBUG_TRACE
+unsigned long long *g_trace = nullptr;
+#endif
+#ifndef RMM_TUNE_LARGE_MIN_TILES
+#define RMM_TUNE_LARGE_MIN_TILES 256
+#endif
+
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int WAVES_K, int AMODE, int BMODE, int OUT>
+hipError_t launch(const GemmArgs &g_in, int splits, hipStream_t stream) {
+    GemmArgs g = g_in;
+#ifdef RMM_DEBUG_TRACE
+    g.trace = (AMODE == RMM_DEBUG_TRACE_A && BMODE == RMM_DEBUG_TRACE_B) ? g_trace : nullptr;
+#endif
     const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     dim3 grid((unsigned)tiles, 1, (unsigned)splits);
     // The kernel runs whole groups of D tiles; take the depth that wastes fewer.
     const int64_t kt = (min(g.K, g.k_chunk) + BK - 1) / BK;
     if constexpr (AMODE == A_GAUSS || AMODE == A_RADEM) {
         // The sketch kernels load one operand only and need their registers for wide wave tiles.
-        gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, AMODE, BMODE, OUT, RMM_TUNE_SK_D>
-            <<<grid, 64 * WAVES_M * WAVES_N, 0, stream>>>(g);
+        gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, WAVES_K, AMODE, BMODE, OUT, RMM_TUNE_SK_D>
+            <<<grid, 64 * WAVES_M * WAVES_N * WAVES_K, 0, stream>>>(g);
         return hipGetLastError();
     }
     const int64_t pad1 = (kt + RMM_TUNE_D1 - 1) / RMM_TUNE_D1 * RMM_TUNE_D1 - kt;
     const int64_t pad2 = (kt + RMM_TUNE_D2 - 1) / RMM_TUNE_D2 * RMM_TUNE_D2 - kt;
     if (pad1 <= pad2)
-        gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, AMODE, BMODE, OUT, RMM_TUNE_D1>
-            <<<grid, 64 * WAVES_M * WAVES_N, 0, stream>>>(g);
+        gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, WAVES_K, AMODE, BMODE, OUT, RMM_TUNE_D1>
+            <<<grid, 64 * WAVES_M * WAVES_N * WAVES_K, 0, stream>>>(g);
     else
-        gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, AMODE, BMODE, OUT, RMM_TUNE_D2>
-            <<<grid, 64 * WAVES_M * WAVES_N, 0, stream>>>(g);
+        gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, WAVES_K, AMODE, BMODE, OUT, RMM_TUNE_D2>
+            <<<grid, 64 * WAVES_M * WAVES_N * WAVES_K, 0, stream>>>(g);
     return hipGetLastError();
 }
 
+// Large outputs: 256x256 tiles (half the operand traffic per flop), one work-group per compute
+// unit, prefetch depth 3.  Worth it once there is at least one such tile per compute unit.
+template <int AMODE, int BMODE>
+hipError_t launch_large(const GemmArgs &g_in, hipStream_t stream) {
+    GemmArgs g = g_in;
+#ifdef RMM_DEBUG_TRACE
+    g.trace = nullptr;
+#endif
+    const int64_t tiles = ((g.M + 255) / 256) * ((g.N + 255) / 256);
+    gemm_mfma_kernel<256, 256, 32, 2, 2, 1, AMODE, BMODE, OUT_BF16, 3><<<dim3((unsigned)tiles), 256, 0, stream>>>(g);
+    return hipGetLastError();
+}
+
+bool large_tiles_pay(int64_t m, int64_t n) { return ((m + 255) / 256) * ((n + 255) / 256) >= RMM_TUNE_LARGE_MIN_TILES; }
+
 }  // namespace
 
-// Tile shapes: BM, BN, BK, waves along M, waves along N.
+// Tile shapes: BM, BN, BK, waves along M, waves along N, wave groups along the contraction.
 #ifndef RMM_TUNE_NT
-#define RMM_TUNE_NT 128, 128, 64, 2, 2
+#define RMM_TUNE_NT 128, 128, 32, 2, 2, 1
 #endif
 #ifndef RMM_TUNE_NN
-#define RMM_TUNE_NN 128, 128, 64, 2, 2
+#define RMM_TUNE_NN 128, 128, 32, 2, 2, 1
 #endif
 #ifndef RMM_TUNE_DW
-#define RMM_TUNE_DW 128, 128, 64, 2, 2
+#define RMM_TUNE_DW 128, 128, 32, 2, 2, 1
 #endif
 #ifndef RMM_TUNE_SK
-#define RMM_TUNE_SK 128, 256, 64, 4, 1
+#define RMM_TUNE_SK 128, 256, 64, 4, 1, 1
 #endif
 #ifndef RMM_TUNE_SK_BM
 #define RMM_TUNE_SK_BM 128
@@ -684,6 +771,10 @@ hipError_t launch(const GemmArgs &g, int splits, hipStream_t stream) {
 #define RMM_TUNE_SMALLK_D2 4
 #endif
 
+#ifdef RMM_DEBUG_TRACE
+extern "C" void rmm_debug_set_trace(void *p) { g_trace = (unsigned long long *)p; }
+#endif
+
 bool mfma_shape_ok(int64_t n, int64_t d_in, int64_t d_out, int64_t k) {
     // 16-byte chunks need widths that are multiples of 8; buffer loads need operands below 2^31 bytes.
     const int64_t lim = ((int64_t)1 << 31) / 2;
@@ -697,6 +788,7 @@ hipError_t launch_linear_nt_bf16(const bf16_t *X, const bf16_t *W, const bf16_t 
     g.A = X, g.lda = d_in, g.B = W, g.ldb = d_in, g.C = Y, g.ldc = d_out, g.bias = bias;
     g.M = n, g.N = d_out, g.K = d_in, g.alpha = 1.0f, g.k_chunk = (d_in + 127) / 128 * 128;
     g.a_bytes = n * d_in * 2, g.b_bytes = d_out * d_in * 2;
+    if (large_tiles_pay(g.M, g.N)) return launch_large<A_KCONTIG, B_KCONTIG>(g, stream);
     return launch<RMM_TUNE_NT, A_KCONTIG, B_KCONTIG, OUT_BF16>(g, 1, stream);
 }
 
@@ -706,6 +798,7 @@ hipError_t launch_linear_nn_bf16(const bf16_t *dY, const bf16_t *W, bf16_t *dX, 
     g.A = dY, g.lda = d_out, g.B = W, g.ldb = d_in, g.C = dX, g.ldc = d_in, g.bias = nullptr;
     g.M = n, g.N = d_in, g.K = d_out, g.alpha = 1.0f, g.k_chunk = (d_out + 127) / 128 * 128;
     g.a_bytes = n * d_out * 2, g.b_bytes = d_out * d_in * 2;
+    if (large_tiles_pay(g.M, g.N)) return launch_large<A_KCONTIG, B_NCONTIG>(g, stream);
     return launch<RMM_TUNE_NN, A_KCONTIG, B_NCONTIG, OUT_BF16>(g, 1, stream);
 }
 
@@ -715,6 +808,7 @@ hipError_t launch_dw_bf16(const bf16_t *G, const bf16_t *X_proj, bf16_t *dW, int
     g.A = G, g.lda = d_out, g.B = X_proj, g.ldb = d_in, g.C = dW, g.ldc = d_in, g.bias = nullptr;
     g.M = d_out, g.N = d_in, g.K = k, g.alpha = 1.0f, g.k_chunk = (k + 127) / 128 * 128;
     g.a_bytes = k * d_out * 2, g.b_bytes = k * d_in * 2;
+    if (large_tiles_pay(g.M, g.N)) return launch_large<A_MCONTIG, B_NCONTIG>(g, stream);
     return launch<RMM_TUNE_DW, A_MCONTIG, B_NCONTIG, OUT_BF16>(g, 1, stream);
 }
 

@@ -112,6 +112,16 @@ def test_small_and_ragged(dtype, kind, shape):
     check_layer(X, W, dY, k, kind, 0xABCDEF, 42, dtype, bias=bias, label="ragged %s %s %s" % (shape, dtype, kind))
 
 
+@pytest.mark.parametrize("kind", [rmm.GAUSSIAN, rmm.RADEMACHER])
+def test_large_tiles_ragged(kind):
+    """Every output (Y, dX, dW) has at least 256 tiles of 256 x 256, the point where the
+    library switches to its large tile, and every dimension leaves a ragged tail there."""
+    n, d_in, d_out, k = 4100, 3848, 3848, 100
+    X, W, dY = synth.layer_inputs(n, d_in, d_out, "bf16", (21, 22, 23), w_std=1.0 / math.sqrt(d_in))
+    bias = synth.to_torch(synth.normal((d_out,), 24), "bf16")
+    check_layer(X, W, dY, k, kind, 0x5EED, 7, "bf16", bias=bias, label="large ragged kind=%d" % kind)
+
+
 def test_config2_base_attention():
     c = synth.CONFIGS["c2_base_attn"]
     X, W, dY = synth.config_inputs("c2_base_attn")
