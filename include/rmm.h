@@ -119,7 +119,12 @@ typedef enum {
     RMM_STAGE_BWD_DX = 2,     /* dX = dY W                   */
     RMM_STAGE_BWD_G = 3,      /* G = S^T dY (into workspace) */
     RMM_STAGE_BWD_DW = 4,     /* dW = G^T X_proj             */
-    RMM_STAGE_BWD_DBIAS = 5   /* dbias = dY^T 1              */
+    RMM_STAGE_BWD_DBIAS = 5,  /* dbias = dY^T 1              */
+    /* The product kernel of a sketch stage alone, without the kernel that sums
+     * the token-slice partial results (identical to the stage when the library
+     * uses a single slice). */
+    RMM_STAGE_FWD_XPROJ_PRODUCT = 6,
+    RMM_STAGE_BWD_G_PRODUCT = 7
 } rmm_stage_t;
 
 /* Measurement hooks: identical to rmm_forward / rmm_backward, and in addition
@@ -133,6 +138,13 @@ int rmm_forward_profiled(const rmm_layer_desc_t *desc, rmm_rng_state_t state, co
 int rmm_backward_profiled(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *dY, const void *W,
                           const void *X_proj, void *dX, void *dW, void *dbias, void *ws, size_t ws_bytes,
                           void *stream, int stage, void *ev_begin, void *ev_end);
+
+/* rmm_sketch with an event pair recorded around its product kernel alone (the
+ * kernel that reads A), as RMM_STAGE_FWD_XPROJ_PRODUCT does inside a forward
+ * pass.  Either event may be NULL, which records nothing. */
+int rmm_sketch_profiled(int64_t n, int64_t d, int64_t k, int dtype, int kind, rmm_rng_state_t state,
+                        const void *A, void *A_proj, void *ws, size_t ws_bytes, void *stream,
+                        void *ev_begin, void *ev_end);
 
 /* Test hooks for the bit-exactness requirement on the generator.
  *

@@ -53,6 +53,8 @@ def load_library():
     L.rmm_workspace_bytes.argtypes = [ctypes.POINTER(_Desc), ci]
     L.rmm_sketch.restype = ci
     L.rmm_sketch.argtypes = [i64, i64, i64, ci, ci, _State, vp, vp, vp, sz, vp]
+    L.rmm_sketch_profiled.restype = ci
+    L.rmm_sketch_profiled.argtypes = L.rmm_sketch.argtypes + [vp, vp]
     L.rmm_forward.restype = ci
     L.rmm_forward.argtypes = [ctypes.POINTER(_Desc), _State, vp, vp, vp, vp, vp, vp, sz, vp]
     L.rmm_backward.restype = ci
@@ -113,21 +115,26 @@ def _workspace(ws, need, device):
     return ws, ctypes.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size()
 
 
-def rmm_sketch(A, k, kind, seed, offset, out=None, ws=None):
-    """A (n x d) -> S^T A (k x d).  Returns `out`."""
+def rmm_sketch(A, k, kind, seed, offset, out=None, ws=None, events=None):
+    """A (n x d) -> S^T A (k x d).  Returns `out`.  `events` = (begin, end), torch.cuda.Event
+    objects recorded once before, are re-recorded around the product kernel alone."""
     n, d = A.shape
     if out is None:
         out = torch.empty((k, d), dtype=A.dtype, device=A.device)
     need = rmm_workspace_bytes(n, d, d, k, A.dtype, kind, OP_SKETCH)
     ws, wsp, wsb = _workspace(ws, need, A.device)
-    rc = load_library().rmm_sketch(n, d, k, _DTYPES[A.dtype], kind, _State(seed, offset), _ptr(A, "A"),
-                                   _ptr(out, "out", A.dtype, (k, d)), wsp, wsb, _stream(A))
+    evb = eve = None
+    if events is not None:
+        evb, eve = ctypes.c_void_p(events[0].cuda_event), ctypes.c_void_p(events[1].cuda_event)
+    rc = load_library().rmm_sketch_profiled(n, d, k, _DTYPES[A.dtype], kind, _State(seed, offset), _ptr(A, "A"),
+                                            _ptr(out, "out", A.dtype, (k, d)), wsp, wsb, _stream(A), evb, eve)
     if rc != 0:
         raise RmmError(rc, "rmm_sketch")
     return out
 
 
 STAGE_FWD_Y, STAGE_FWD_XPROJ, STAGE_BWD_DX, STAGE_BWD_G, STAGE_BWD_DW, STAGE_BWD_DBIAS = range(6)
+STAGE_FWD_XPROJ_PRODUCT, STAGE_BWD_G_PRODUCT = 6, 7
 
 
 def _event_args(profile):

@@ -74,9 +74,12 @@ private:
 
 template <typename T>
 int sketch_impl(int64_t n, int64_t d, int64_t k, int kind, SketchState st, const void *A, void *out, bool mfma,
-                void *ws, hipStream_t stream) {
+                void *ws, hipStream_t stream, const StageEvents &ev = StageEvents(), int product_stage = RMM_STAGE_NONE) {
+    const bool timed = product_stage != RMM_STAGE_NONE && ev.stage == product_stage;
     if (mfma)
-        return from_hip(launch_sketch_bf16((const bf16_t *)A, (bf16_t *)out, n, d, k, kind, st, ws, stream));
+        return from_hip(launch_sketch_bf16((const bf16_t *)A, (bf16_t *)out, n, d, k, kind, st, ws, stream,
+                                           timed ? ev.begin : nullptr, timed ? ev.end : nullptr));
+    StageScope scope(ev, product_stage, stream);  // the plain path is one kernel
     const float alpha = 1.0f / sqrtf((float)k);
     return from_hip(launch_sketch_plain<T, T>((const T *)A, (T *)out, n, d, k, kind, st, alpha, stream));
 }
@@ -95,7 +98,8 @@ int forward_impl(const rmm_layer_desc_t *d, SketchState st, const void *X, const
         if (e != hipSuccess) return RMM_ERR_LAUNCH;
     }
     StageScope scope(ev, RMM_STAGE_FWD_XPROJ, stream);
-    return sketch_impl<T>(d->n, d->d_in, d->k, d->kind, st, X, X_proj, mfma, ws, stream);
+    return sketch_impl<T>(d->n, d->d_in, d->k, d->kind, st, X, X_proj, mfma, ws, stream, ev,
+                          RMM_STAGE_FWD_XPROJ_PRODUCT);
 }
 
 template <typename T>
@@ -114,7 +118,8 @@ int backward_impl(const rmm_layer_desc_t *d, SketchState st, const void *dY, con
     T *G = (T *)ws;  // G = S^T dY, k x d_out
     {
         StageScope scope(ev, RMM_STAGE_BWD_G, stream);
-        int rc = sketch_impl<T>(d->n, d->d_out, d->k, d->kind, st, dY, G, mfma, (char *)ws + g_bytes(d), stream);
+        int rc = sketch_impl<T>(d->n, d->d_out, d->k, d->kind, st, dY, G, mfma, (char *)ws + g_bytes(d), stream, ev,
+                                RMM_STAGE_BWD_G_PRODUCT);
         if (rc != RMM_OK) return rc;
     }
     {   // dW = G^T X_proj: A(r, kk) = G[kk][r], B(kk, c) = X_proj[kk][c]
@@ -163,8 +168,8 @@ size_t rmm_workspace_bytes(const rmm_layer_desc_t *desc, int op) {
     }
 }
 
-int rmm_sketch(int64_t n, int64_t d, int64_t k, int dtype, int kind, rmm_rng_state_t state, const void *A,
-               void *A_proj, void *ws, size_t ws_bytes, void *stream) {
+int rmm_sketch_profiled(int64_t n, int64_t d, int64_t k, int dtype, int kind, rmm_rng_state_t state, const void *A,
+                        void *A_proj, void *ws, size_t ws_bytes, void *stream, void *ev_begin, void *ev_end) {
     rmm_layer_desc_t desc = {n, d, d, k, dtype, kind};
     if (!desc_ok(&desc) || A == nullptr || A_proj == nullptr) return RMM_ERR_INVALID_ARG;
     if (!aligned16(A) || !aligned16(A_proj) || !aligned16(ws)) return RMM_ERR_INVALID_ARG;
@@ -174,8 +179,18 @@ int rmm_sketch(int64_t n, int64_t d, int64_t k, int dtype, int kind, rmm_rng_sta
     const SketchState st = make_state(state.seed, state.offset);
     hipStream_t s = (hipStream_t)stream;
     const bool mfma = use_mfma(&desc);
-    return dtype == RMM_DTYPE_BF16 ? sketch_impl<bf16_t>(n, d, k, kind, st, A, A_proj, mfma, ws, s)
-                                   : sketch_impl<float>(n, d, k, kind, st, A, A_proj, false, ws, s);
+    StageEvents ev;
+    ev.stage = RMM_STAGE_FWD_XPROJ_PRODUCT;
+    ev.begin = (hipEvent_t)ev_begin;
+    ev.end = (hipEvent_t)ev_end;
+    return dtype == RMM_DTYPE_BF16
+               ? sketch_impl<bf16_t>(n, d, k, kind, st, A, A_proj, mfma, ws, s, ev, RMM_STAGE_FWD_XPROJ_PRODUCT)
+               : sketch_impl<float>(n, d, k, kind, st, A, A_proj, false, ws, s, ev, RMM_STAGE_FWD_XPROJ_PRODUCT);
+}
+
+int rmm_sketch(int64_t n, int64_t d, int64_t k, int dtype, int kind, rmm_rng_state_t state, const void *A,
+               void *A_proj, void *ws, size_t ws_bytes, void *stream) {
+    return rmm_sketch_profiled(n, d, k, dtype, kind, state, A, A_proj, ws, ws_bytes, stream, nullptr, nullptr);
 }
 
 int rmm_forward_profiled(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *X, const void *W,

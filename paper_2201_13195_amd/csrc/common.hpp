@@ -54,6 +54,8 @@ hipError_t launch_colsum(const T *A, T *out, int64_t n, int64_t d, hipStream_t s
 
 // bf16 MFMA path (mfma.hip).  Usable when mfma_shape_ok(); `ws` for the sketch
 // must hold sketch_workspace_bf16() bytes (fp32 partial sums of the token slices).
+// launch_sketch_bf16 records the optional event pair around its product kernel
+// alone (the sum over token slices, when there is one, comes after `ev_end`).
 bool mfma_shape_ok(int64_t n, int64_t d_in, int64_t d_out, int64_t k);
 hipError_t launch_linear_nt_bf16(const bf16_t *X, const bf16_t *W, const bf16_t *bias, bf16_t *Y, int64_t n,
                                  int64_t d_in, int64_t d_out, hipStream_t stream);
@@ -63,7 +65,8 @@ hipError_t launch_dw_bf16(const bf16_t *G, const bf16_t *X_proj, bf16_t *dW, int
                           hipStream_t stream);
 size_t sketch_workspace_bf16(int64_t n, int64_t d, int64_t k);
 hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d, int64_t k, int kind, SketchState st,
-                              void *ws, hipStream_t stream);
+                              void *ws, hipStream_t stream, hipEvent_t ev_begin = nullptr,
+                              hipEvent_t ev_end = nullptr);
 
 hipError_t launch_debug_philox(SketchState st, uint32_t c0, uint32_t c1, int64_t ncalls, uint32_t *out,
                                hipStream_t stream);

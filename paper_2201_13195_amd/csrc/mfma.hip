@@ -853,9 +853,26 @@ static hipError_t launch_smallk(const SmallkArgs &g, int slices, hipStream_t str
     return hipGetLastError();
 }
 
+namespace {
+// Brackets the product kernel (not the sum over token slices) with the caller's events.
+struct ProductEvents {
+    hipEvent_t begin, end;
+    hipStream_t stream;
+    ProductEvents(hipEvent_t b, hipEvent_t e, hipStream_t s) : begin(b), end(e), stream(s) {
+        if (begin != nullptr && end != nullptr) (void)hipEventRecord(begin, stream);
+    }
+    void done() {
+        if (begin != nullptr && end != nullptr) (void)hipEventRecord(end, stream);
+        begin = end = nullptr;
+    }
+    ~ProductEvents() { done(); }
+};
+}  // namespace
+
 hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d, int64_t k, int kind, SketchState st,
-                              void *ws, hipStream_t stream) {
+                              void *ws, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end) {
     const float alpha = 1.0f / sqrtf((float)k);
+    ProductEvents pev(ev_begin, ev_end, stream);
     if (k <= kSmallK) {  // bound by one pass over A: streaming kernel
         SmallkArgs a{};
         a.A = A, a.n = n, a.d = d, a.k = k, a.a_bytes = n * d * 2, a.st = st;
@@ -863,6 +880,7 @@ hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d
         a.C = slices == 1 ? (void *)out : ws, a.alpha = alpha;
         hipError_t e = k <= 32 ? (kind == 0 ? launch_smallk<1, 0>(a, slices, stream) : launch_smallk<1, 1>(a, slices, stream))
                                : (kind == 0 ? launch_smallk<2, 0>(a, slices, stream) : launch_smallk<2, 1>(a, slices, stream));
+        pev.done();
         if (e != hipSuccess || slices == 1) return e;
         const int64_t elems = k * d;
         reduce_partials_kernel<<<(unsigned)((elems / 4 + 255) / 256), 256, 0, stream>>>((const float *)ws, out, elems,
@@ -884,6 +902,7 @@ hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d
     g.C = ws, g.alpha = 1.0f, g.split_stride = k * d;
     e = kind == 0 ? launch<RMM_TUNE_SK, A_GAUSS, B_NCONTIG, OUT_F32_PARTIAL>(g, splits, stream)
                   : launch<RMM_TUNE_SK, A_RADEM, B_NCONTIG, OUT_F32_PARTIAL>(g, splits, stream);
+    pev.done();
     if (e != hipSuccess) return e;
     const int64_t elems = k * d;  // d % 8 == 0, so elems % 4 == 0
     reduce_partials_kernel<<<(unsigned)((elems / 4 + 255) / 256), 256, 0, stream>>>((const float *)ws, out, elems,

@@ -210,3 +210,34 @@ def test_workspace_too_small_is_reported():
     with pytest.raises(rmm.RmmError) as e:
         rmm.rmm_backward(dYd, Wd, Xp, rmm.GAUSSIAN, 0, 0, ws=small)
     assert e.value.status == -3
+
+
+def test_profiled_entry_points_time_one_stage_and_change_nothing():
+    """The profiled variants record the caller's events around exactly one stage and
+    compute what the plain entry points compute."""
+    X, W, dY = synth.layer_inputs(2048, 512, 768, "bf16", (31, 32, 33))
+    Xd, Wd, dYd = X.to(DEV), W.to(DEV), dY.to(DEV)
+    k, kind = 205, rmm.GAUSSIAN
+    Y0, Xp0 = rmm.rmm_forward(Xd, Wd, None, k, kind, 9, 1)
+    dX0, dW0, _ = rmm.rmm_backward(dYd, Wd, Xp0, kind, 9, 1)
+    ms = {}
+    for stage in range(8):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(); b.record()
+        torch.cuda.synchronize()
+        Y1, Xp1 = rmm.rmm_forward(Xd, Wd, None, k, kind, 9, 1, profile=(stage, a, b))
+        dX1, dW1, _ = rmm.rmm_backward(dYd, Wd, Xp1, kind, 9, 1, profile=(stage, a, b))
+        torch.cuda.synchronize()
+        ms[stage] = a.elapsed_time(b)
+        assert torch.equal(Y0, Y1) and torch.equal(Xp0, Xp1) and torch.equal(dX0, dX1) and torch.equal(dW0, dW1)
+    print("stage ms", ms, flush=True)
+    for stage in (0, 1, 2, 3, 4, 6, 7):
+        assert 0.0 < ms[stage] < 50.0, (stage, ms)
+    # a product kernel is part of its stage
+    assert ms[6] <= ms[1] * 1.5 + 0.02 and ms[7] <= ms[3] * 1.5 + 0.02
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(); b.record()
+    torch.cuda.synchronize()
+    Xp2 = rmm.rmm_sketch(Xd, k, kind, 9, 1, events=(a, b))
+    torch.cuda.synchronize()
+    assert torch.equal(Xp2, Xp0) and 0.0 < a.elapsed_time(b) < 50.0
