@@ -21,6 +21,8 @@
 // accumulator, so P is exact in bf16 for Rademacher and rounded once for Gaussian.
 #include "common.hpp"
 
+#include <type_traits>
+
 namespace rmm {
 
 namespace {
@@ -398,47 +400,72 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) gemm_mfma_ke
     // wave passes a strip of 32 rows x 128 bytes through a private piece of LDS and writes it out
     // with 16 bytes per lane, 8 lanes per row (full 128-byte lines).
     __syncthreads();  // all fragment reads of the main loop are done; LDS is free
-    if constexpr (WAVES_K > 1) {
-        // Sum the accumulators of the WAVES_K wave groups into group 0: the other groups park theirs
-        // in LDS, 16 bytes per lane and run, laid out so that consecutive lanes are consecutive.
-        constexpr int GROUP_THREADS = 64 * WAVES_M * WAVES_N;
-        constexpr int RUNS = T::TM * T::TN * 4;
-        static_assert((WAVES_K - 1) * RUNS * GROUP_THREADS * 16 <= T::LDS_BYTES, "accumulators of the other groups fit in LDS");
+    // Two wave groups that split the contraction each end up owning half of the 32x32 tiles of
+    // their (identical) wave tile: a group parks the tiles the other one owns in LDS, 16 bytes per
+    // lane and run with consecutive lanes consecutive, in rounds that fit the LDS, and adds what
+    // the other group parked for it.  Both groups then write their halves.
+    static_assert(WAVES_K <= 2, "the cross-group sum is written for two groups");
+    constexpr int P = T::TM * T::TN;  // tiles per wave, numbered a * TN + b
+    constexpr int OWN = P / WAVES_K;  // group kg owns tiles kg*OWN .. kg*OWN + OWN - 1
+    if constexpr (WAVES_K == 2) {
+        static_assert(P % 2 == 0, "an even number of tiles per wave");
+        constexpr int CH_MAX = T::LDS_BYTES / (64 * T::THREADS);  // tiles per thread and round that fit
+        static_assert(CH_MAX >= 1, "one tile per thread fits in LDS");
+        constexpr int CH = OWN < CH_MAX ? OWN : CH_MAX;
         float4 *park = reinterpret_cast<float4 *>(lds);
-        const int tg = tid % GROUP_THREADS;
-        if (kg > 0) {
+        constexpr int GROUP_THREADS = T::THREADS / 2;
+        const int partner = kg == 0 ? tid + GROUP_THREADS : tid - GROUP_THREADS;
+        // `first` is a literal at every call, so all accumulator indices are static after unrolling.
+        auto park_tiles = [&](auto first, int c0) {
 #pragma unroll
-            for (int a = 0; a < T::TM; ++a)
-#pragma unroll
-                for (int b = 0; b < T::TN; ++b)
+            for (int c = 0; c < CH; ++c) {
+                const int p = decltype(first)::value + c0 + c;
+                if (c0 + c < OWN) {
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
-                        park[((kg - 1) * RUNS + (a * T::TN + b) * 4 + q) * GROUP_THREADS + tg] =
-                            make_float4(acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
+                        park[(c * 4 + q) * T::THREADS + tid] =
+                            make_float4(acc[p / T::TN][p % T::TN][4 * q], acc[p / T::TN][p % T::TN][4 * q + 1],
+                                        acc[p / T::TN][p % T::TN][4 * q + 2], acc[p / T::TN][p % T::TN][4 * q + 3]);
+                }
+            }
+        };
+        auto add_tiles = [&](auto first, int c0) {
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const int p = decltype(first)::value + c0 + c;
+                if (c0 + c < OWN) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float4 pv = park[(c * 4 + q) * T::THREADS + partner];
+                        acc[p / T::TN][p % T::TN][4 * q] += pv.x, acc[p / T::TN][p % T::TN][4 * q + 1] += pv.y;
+                        acc[p / T::TN][p % T::TN][4 * q + 2] += pv.z, acc[p / T::TN][p % T::TN][4 * q + 3] += pv.w;
+                    }
+                }
+            }
+        };
+        using Zero = std::integral_constant<int, 0>;
+        using Half = std::integral_constant<int, OWN>;
+#pragma unroll
+        for (int c0 = 0; c0 < OWN; c0 += CH) {
+            if (kg == 0)
+                park_tiles(Half(), c0);  // group 0 gives away the upper half
+            else
+                park_tiles(Zero(), c0);
+            __syncthreads();
+            if (kg == 0)
+                add_tiles(Zero(), c0);
+            else
+                add_tiles(Half(), c0);
+            __syncthreads();
         }
-        __syncthreads();
-        if (kg == 0) {
-#pragma unroll
-            for (int o = 1; o < WAVES_K; ++o)
-#pragma unroll
-                for (int a = 0; a < T::TM; ++a)
-#pragma unroll
-                    for (int b = 0; b < T::TN; ++b)
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const float4 p = park[((o - 1) * RUNS + (a * T::TN + b) * 4 + q) * GROUP_THREADS + tg];
-                            acc[a][b][4 * q] += p.x, acc[a][b][4 * q + 1] += p.y;
-                            acc[a][b][4 * q + 2] += p.z, acc[a][b][4 * q + 3] += p.w;
-                        }
-        }
-        __syncthreads();
     }
-    if (kg == 0) {
+    {
         constexpr int EB = OUT == OUT_BF16 ? 2 : 4;         // bytes per output element
         constexpr int CW = 128 / EB;                         // columns per strip: 64 (bf16) or 32 (fp32)
         constexpr int TPS = CW / 32;                         // 32-column MFMA tiles per strip
         constexpr int PITCH = 128 + 16;                      // bytes per strip row in LDS
         static_assert(T::THREADS / 64 * 32 * PITCH <= T::LDS_BYTES, "staging area fits in LDS");
+        static_assert(WAVES_K == 1 || (OWN % TPS == 0 && T::TN % TPS == 0), "no strip straddles the two groups' tiles");
         char *stage = reinterpret_cast<char *>(lds) + wave * 32 * PITCH;
         const int r = lane & 31, h = lane >> 5;
 #pragma unroll
@@ -446,6 +473,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) gemm_mfma_ke
             const int64_t row0 = m0 + wm * T::WTM + a * 32;
 #pragma unroll
             for (int b0 = 0; b0 < T::TN; b0 += TPS) {
+                if (WAVES_K > 1 && (a * T::TN + b0) / OWN != kg) continue;  // the other group's tiles
                 const int64_t col0 = n0 + wn * T::WTN + b0 * 32;
 #pragma unroll
                 for (int bb = 0; bb < TPS; ++bb) {
@@ -751,7 +779,7 @@ bool large_tiles_pay(int64_t m, int64_t n) { return ((m + 255) / 256) * ((n + 25
 #define RMM_TUNE_DW 128, 128, 32, 2, 2, 1
 #endif
 #ifndef RMM_TUNE_SK
-#define RMM_TUNE_SK 128, 256, 64, 4, 1, 1
+#define RMM_TUNE_SK 128, 256, 64, 4, 1, 2
 #endif
 #ifndef RMM_TUNE_SK_BM
 #define RMM_TUNE_SK_BM 128

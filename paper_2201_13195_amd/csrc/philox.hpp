@@ -28,15 +28,16 @@ struct Words4 {
 };
 
 // One Philox-4x32-10 block: ten rounds, key bumped by the Weyl constants before
-// rounds 2..10.  The two 32x32->64 products per round map to v_mad_u64_u32.
+// rounds 2..10.  The two 32x32->64 products per round map to v_mad_u64_u32 and each
+// three-way xor to one v_bitop3_b32 (truth table 0x96 = a ^ b ^ c).
 __device__ __forceinline__ Words4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                                 uint32_t k0, uint32_t k1) {
 #pragma unroll
     for (int r = 0; r < 10; ++r) {
         const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
         const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n0 = __builtin_amdgcn_bitop3_b32((uint32_t)(p1 >> 32), c1, k0, 0x96);
+        const uint32_t n2 = __builtin_amdgcn_bitop3_b32((uint32_t)(p0 >> 32), c3, k1, 0x96);
         c1 = (uint32_t)p1;
         c3 = (uint32_t)p0;
         c0 = n0;
