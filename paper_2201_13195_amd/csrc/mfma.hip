@@ -720,8 +720,14 @@ __global__ void __launch_bounds__(256) sketch_smallk_kernel(SmallkArgs g) {
 #ifdef RMM_DEBUG_TRACE
 unsigned long long *g_trace = nullptr;
 #endif
+#ifndef RMM_TUNE_LARGE
+#define RMM_TUNE_LARGE 256, 256, 32, 2, 4, 1
+#endif
+#ifndef RMM_TUNE_SPLIT_MIN_K
+#define RMM_TUNE_SPLIT_MIN_K 1536
+#endif
 #ifndef RMM_TUNE_LARGE_MIN_TILES
-#define RMM_TUNE_LARGE_MIN_TILES 256
+#define RMM_TUNE_LARGE_MIN_TILES 160
 #endif
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int WAVES_K, int AMODE, int BMODE, int OUT>
@@ -760,11 +766,18 @@ hipError_t launch_large(const GemmArgs &g_in, hipStream_t stream) {
     g.trace = nullptr;
 #endif
     const int64_t tiles = ((g.M + 255) / 256) * ((g.N + 255) / 256);
-    gemm_mfma_kernel<256, 256, 32, 2, 2, 1, AMODE, BMODE, OUT_BF16, 3><<<dim3((unsigned)tiles), 256, 0, stream>>>(g);
+    typedef Tile<RMM_TUNE_LARGE, AMODE, BMODE, OUT_BF16> T;
+    gemm_mfma_kernel<RMM_TUNE_LARGE, AMODE, BMODE, OUT_BF16, 3><<<dim3((unsigned)tiles), T::THREADS, 0, stream>>>(g);
     return hipGetLastError();
 }
 
 bool large_tiles_pay(int64_t m, int64_t n) { return ((m + 255) / 256) * ((n + 255) / 256) >= RMM_TUNE_LARGE_MIN_TILES; }
+
+// Few 128x128 tiles (at most one per compute unit) and a long contraction: two wave groups per
+// tile split the contraction, so that a compute unit still holds eight waves.
+bool split_waves_pay(int64_t m, int64_t n, int64_t kk) {
+    return ((m + 127) / 128) * ((n + 127) / 128) <= 256 && kk >= RMM_TUNE_SPLIT_MIN_K;
+}
 
 }  // namespace
 
@@ -777,6 +790,9 @@ bool large_tiles_pay(int64_t m, int64_t n) { return ((m + 255) / 256) * ((n + 25
 #endif
 #ifndef RMM_TUNE_DW
 #define RMM_TUNE_DW 128, 128, 32, 2, 2, 1
+#endif
+#ifndef RMM_TUNE_SPLIT
+#define RMM_TUNE_SPLIT 128, 128, 64, 2, 2, 2
 #endif
 #ifndef RMM_TUNE_SK
 #define RMM_TUNE_SK 128, 256, 64, 4, 1, 2
@@ -817,6 +833,7 @@ hipError_t launch_linear_nt_bf16(const bf16_t *X, const bf16_t *W, const bf16_t 
     g.M = n, g.N = d_out, g.K = d_in, g.alpha = 1.0f, g.k_chunk = (d_in + 127) / 128 * 128;
     g.a_bytes = n * d_in * 2, g.b_bytes = d_out * d_in * 2;
     if (large_tiles_pay(g.M, g.N)) return launch_large<A_KCONTIG, B_KCONTIG>(g, stream);
+    if (split_waves_pay(g.M, g.N, g.K)) return launch<RMM_TUNE_SPLIT, A_KCONTIG, B_KCONTIG, OUT_BF16>(g, 1, stream);
     return launch<RMM_TUNE_NT, A_KCONTIG, B_KCONTIG, OUT_BF16>(g, 1, stream);
 }
 
@@ -827,6 +844,7 @@ hipError_t launch_linear_nn_bf16(const bf16_t *dY, const bf16_t *W, bf16_t *dX, 
     g.M = n, g.N = d_in, g.K = d_out, g.alpha = 1.0f, g.k_chunk = (d_out + 127) / 128 * 128;
     g.a_bytes = n * d_out * 2, g.b_bytes = d_out * d_in * 2;
     if (large_tiles_pay(g.M, g.N)) return launch_large<A_KCONTIG, B_NCONTIG>(g, stream);
+    if (split_waves_pay(g.M, g.N, g.K)) return launch<RMM_TUNE_SPLIT, A_KCONTIG, B_NCONTIG, OUT_BF16>(g, 1, stream);
     return launch<RMM_TUNE_NN, A_KCONTIG, B_NCONTIG, OUT_BF16>(g, 1, stream);
 }
 
@@ -837,6 +855,7 @@ hipError_t launch_dw_bf16(const bf16_t *G, const bf16_t *X_proj, bf16_t *dW, int
     g.M = d_out, g.N = d_in, g.K = k, g.alpha = 1.0f, g.k_chunk = (k + 127) / 128 * 128;
     g.a_bytes = k * d_out * 2, g.b_bytes = k * d_in * 2;
     if (large_tiles_pay(g.M, g.N)) return launch_large<A_MCONTIG, B_NCONTIG>(g, stream);
+    if (split_waves_pay(g.M, g.N, g.K)) return launch<RMM_TUNE_SPLIT, A_MCONTIG, B_NCONTIG, OUT_BF16>(g, 1, stream);
     return launch<RMM_TUNE_DW, A_MCONTIG, B_NCONTIG, OUT_BF16>(g, 1, stream);
 }
 

@@ -122,6 +122,17 @@ def test_large_tiles_ragged(kind):
     check_layer(X, W, dY, k, kind, 0x5EED, 7, "bf16", bias=bias, label="large ragged kind=%d" % kind)
 
 
+@pytest.mark.parametrize("kind", [rmm.GAUSSIAN, rmm.RADEMACHER])
+def test_long_contractions_few_tiles(kind):
+    """Few output tiles and contractions of more than 1536 in all three products (d_in for Y,
+    d_out for dX, k for dW; k > n): the shapes where two wave groups split the contraction
+    of a tile.  Every dimension is ragged."""
+    n, d_in, d_out, k = 300, 1544, 1608, 1550
+    X, W, dY = synth.layer_inputs(n, d_in, d_out, "bf16", (41, 42, 43), w_std=1.0 / math.sqrt(d_in))
+    bias = synth.to_torch(synth.normal((d_out,), 44), "bf16")
+    check_layer(X, W, dY, k, kind, 0xC0FFEE, 3, "bf16", bias=bias, label="long contraction kind=%d" % kind)
+
+
 def test_config2_base_attention():
     c = synth.CONFIGS["c2_base_attn"]
     X, W, dY = synth.config_inputs("c2_base_attn")
