@@ -365,6 +365,11 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) gemm_mfma_ke
 #pragma unroll
         for (int s = 0; s < D; ++s) {
             const int t = grp * D + s;
+            // A step past the end costs little when both operands are loaded (all zeros, no branch);
+            // with a generated operand it would cost a full step of generator work, so leave
+            // (only the last group can be short; the outer loop ends with it).
+            if constexpr (!T::A_IN_LDS)
+                if (t >= num_tiles) break;
             const int64_t kk_t = kk_begin + (int64_t)(t < num_tiles ? rotated(t) : 0) * BK;
             const int64_t kk_n = kk_begin + (int64_t)(t + 1 < num_tiles ? rotated(t + 1) : 0) * BK;
             const int st_next = st_cur == 2 ? 0 : st_cur + 1, st_write = st_next == 2 ? 0 : st_next + 1;
