@@ -83,7 +83,7 @@ def cpu_baseline(cfg, kind, budget_s=10.0):
         step()
         reps += 1
         dt = time.perf_counter() - t0
-        if dt >= budget_s or reps >= 20:
+        if dt >= budget_s or reps >= 500:
             break
     return {"value": fl * reps / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
             "sample": "%d full forward+backward step(s) of the same workload in fp64 numpy, %.1f s" % (reps, dt),
