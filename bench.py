@@ -128,12 +128,70 @@ def sketch_roofline(torch, rmm, binding, dev, kind, kind_name, n=16384, d=4096, 
             "avg_call_ms": cms, "algorithmic_bytes_per_launch": nbytes}
 
 
+def bench_stack(args, torch, rmm, synth, dev, kind):
+    """The 24-block stack of RoBERTa-large-shaped layers (144 layers, N = 16384, k = 1638): a step
+    is the forward sweep that keeps only X_proj + state per layer, then the backward sweep in
+    reverse order.  Inputs of one shape are shared by all layers of that shape (device draws);
+    every layer has its own sketch state and its own resident X_proj."""
+    S, layers = synth.STACK, synth.stack_layers()
+    n, k = S["n"], S["k"]
+    g = torch.Generator(device=dev)
+    g.manual_seed(S["pool_seed_base"])
+    pool, ws_bytes = {}, 16
+    for L in layers:
+        if L["shape"] not in pool:
+            pool[L["shape"]] = dict(
+                X=torch.randn((n, L["d_in"]), device=dev, generator=g).bfloat16(),
+                W=(0.02 * torch.randn((L["d_out"], L["d_in"]), device=dev, generator=g)).bfloat16(),
+                dY=torch.randn((n, L["d_out"]), device=dev, generator=g).bfloat16(),
+                Y=torch.empty((n, L["d_out"]), dtype=torch.bfloat16, device=dev),
+                dX=torch.empty((n, L["d_in"]), dtype=torch.bfloat16, device=dev),
+                dW=torch.empty((L["d_out"], L["d_in"]), dtype=torch.bfloat16, device=dev))
+        for op in (0, 1):
+            ws_bytes = max(ws_bytes, rmm.rmm_workspace_bytes(n, L["d_in"], L["d_out"], k, torch.bfloat16, kind, op))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    xproj = [torch.empty((k, L["d_in"]), dtype=torch.bfloat16, device=dev) for L in layers]
+
+    def step():
+        for L in layers:
+            b = pool[L["shape"]]
+            rmm.rmm_forward(b["X"], b["W"], None, k, kind, L["seed"], L["offset"], Y=b["Y"], X_proj=xproj[L["layer"]], ws=ws)
+        for L in reversed(layers):
+            b = pool[L["shape"]]
+            rmm.rmm_backward(b["dY"], b["W"], xproj[L["layer"]], kind, L["seed"], L["offset"], dX=b["dX"], dW=b["dW"], ws=ws)
+
+    steps, warmup = min(args.steps, 20), min(args.warmup, 3)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    flops = sum(sum(stage_flops(n, L["d_in"], L["d_out"], k).values()) for L in layers)
+    saved = sum(k * L["d_in"] * 2 + 16 for L in layers)
+    plain = sum(n * L["d_in"] * 2 for L in layers)
+    print(json.dumps({
+        "metric": "RMM 24-block stack fwd+bwd TFLOP/s (executed flops of Algorithm 1), N=16384, d=1024/4096, k=1638",
+        "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "c5_stack: 24 x (4 x 1024->1024, 1024->4096, 4096->1024), N=16384 tokens, k=1638 (%s), "
+                               "bf16, all 144 X_proj resident" % args.kind,
+                   "flops_per_step": flops, "saved_activation_bytes": saved, "plain_layer_saved_bytes": plain,
+                   "saved_fraction": saved / plain}}))
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c3_base_ffn_up")
+    ap.add_argument("--workload", default="c3_base_ffn_up",
+                    help="a single-layer config of paper_2201_13195_amd.synth.CONFIGS (default: the headline shape) "
+                         "or c5_stack (the 144-layer stack; reports end-to-end time and stored-activation bytes only)")
     ap.add_argument("--kind", default="gaussian", choices=["gaussian", "rademacher"])
     ap.add_argument("--k", type=int, default=0, help="override the sketch size")
     ap.add_argument("--sets", type=int, default=4, help="rotating input/output sets (keeps the working set above the 256 MB last-level cache)")
@@ -166,6 +224,8 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": nbytes, "copy_bytes_written": nbytes, "copies": 5}))
         return 0
+    if args.workload == "c5_stack":
+        return bench_stack(args, torch, rmm, synth, dev, 0 if args.kind == "gaussian" else 1)
     cfg = dict(synth.CONFIGS[args.workload])
     if args.k:
         cfg["k"] = args.k

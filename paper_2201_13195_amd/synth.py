@@ -59,3 +59,37 @@ def layer_inputs(n, d_in, d_out, dtype, seeds, w_std=None):
 def config_inputs(name):
     c = CONFIGS[name]
     return layer_inputs(c["n"], c["d_in"], c["d_out"], c["dtype"], c["seeds"])
+
+
+# ---------------------------------------------------------------------------------------------
+# Config 5: a stack of 24 RoBERTa-large-shaped blocks of six isolated linear layers each
+# (4 attention projections 1024 -> 1024, FFN 1024 -> 4096 and 4096 -> 1024), N = 16384 tokens,
+# k = 1638.  Layer l (0 .. 143) uses the sketch state (seed 5000 + l, offset l).  Inputs come
+# from a pool of three sets per shape (drawn with the seeds below): blocks 0-7 use set 0, blocks
+# 8-15 set 1, blocks 16-23 set 2, so the first, the middle (block 12) and the last block see
+# three different sets.  Drawing 144 independent sets (15 GB) on the host would take minutes
+# and change nothing that is measured.
+STACK = dict(blocks=24, n=16384, d=1024, d_ff=4096, k=1638, dtype="bf16", seed_base=5000, pool_seed_base=5100)
+
+
+def stack_layers():
+    """[(layer index, block, shape name, d_in, d_out, pool set, sketch seed, offset)] in forward order."""
+    out = []
+    for blk in range(STACK["blocks"]):
+        for j in range(6):
+            shape = "attn" if j < 4 else ("ffn_up" if j == 4 else "ffn_down")
+            d_in = STACK["d_ff"] if shape == "ffn_down" else STACK["d"]
+            d_out = STACK["d_ff"] if shape == "ffn_up" else STACK["d"]
+            l = 6 * blk + j
+            out.append(dict(layer=l, block=blk, shape=shape, d_in=d_in, d_out=d_out, pool=min(blk // 8, 2),
+                            seed=STACK["seed_base"] + l, offset=l))
+    return out
+
+
+def stack_pool_inputs(shape, pool):
+    """CPU tensors (X, W, dY) of pool set `pool` (0..2) for shape "attn" / "ffn_up" / "ffn_down"."""
+    idx = ("attn", "ffn_up", "ffn_down").index(shape)
+    d_in = STACK["d_ff"] if shape == "ffn_down" else STACK["d"]
+    d_out = STACK["d_ff"] if shape == "ffn_up" else STACK["d"]
+    s = STACK["pool_seed_base"] + 10 * idx + 3 * pool
+    return layer_inputs(STACK["n"], d_in, d_out, STACK["dtype"], (s, s + 1, s + 2))
