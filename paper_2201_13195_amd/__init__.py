@@ -8,3 +8,4 @@ from .binding import (  # noqa: F401
     GAUSSIAN, RADEMACHER, RmmError, lib_path, load_library, rmm_backward, rmm_debug_philox,
     rmm_debug_sketch_tile, rmm_forward, rmm_sketch, rmm_status_string, rmm_version, rmm_workspace_bytes,
 )
+from .layer import RMMLinear, RMMLinearFunction  # noqa: F401,E402

@@ -1,0 +1,74 @@
+"""GPU: the autograd / nn.Module form of the layer computes exactly what the C ABI calls compute,
+keeps X_proj instead of X, matches the oracle, and its weight gradient is unbiased."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2201_13195_amd as rmm
+from paper_2201_13195_amd import synth
+from oracle import rmm as o_rmm
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def rel(a, b):
+    return float(np.linalg.norm(a - b) / np.linalg.norm(b))
+
+
+@pytest.mark.parametrize("kind", [rmm.GAUSSIAN, rmm.RADEMACHER])
+def test_module_matches_abi_calls_and_oracle(kind):
+    batch, seq, d_in, d_out = 6, 100, 264, 136            # 600 tokens, 3-D input
+    X, W, dY = synth.layer_inputs(batch * seq, d_in, d_out, "bf16", (51, 52, 53))
+    bias = synth.to_torch(synth.normal((d_out,), 54), "bf16")
+    lin = rmm.RMMLinear(d_in, d_out, bias=True, rho=0.25, kind=kind, seed=77, layer_id=3)
+    with torch.no_grad():
+        lin.weight.copy_(W.to(DEV))
+        lin.bias.copy_(bias.to(DEV))
+    Xd = X.to(DEV).reshape(batch, seq, d_in).requires_grad_(True)
+    Y = lin(Xd)
+    assert Y.shape == (batch, seq, d_out)
+    seed, offset = lin.last_state
+    k = lin.sketch_size(batch * seq)
+    assert (seed, offset, k) == (77, 3 << 32, 150)
+    # what autograd keeps for the backward: W and X_proj (k x d_in), not X
+    saved = Y.grad_fn.saved_tensors
+    assert sorted(tuple(t.shape) for t in saved) == sorted([(d_out, d_in), (k, d_in)])
+    Y.backward(dY.to(DEV).reshape(batch, seq, d_out))
+    # identical bits to the plain calls
+    Y0, Xp0 = rmm.rmm_forward(X.to(DEV), W.to(DEV), bias.to(DEV), k, kind, seed, offset)
+    dX0, dW0, db0 = rmm.rmm_backward(dY.to(DEV), W.to(DEV), Xp0, kind, seed, offset, need_dbias=True)
+    assert torch.equal(Y.reshape(-1, d_out), Y0) and torch.equal(Xd.grad.reshape(-1, d_in), dX0)
+    assert torch.equal(lin.weight.grad, dW0) and torch.equal(lin.bias.grad, db0)
+    # and the oracle
+    X64, W64, dY64, b64 = (synth.to_f64(t) for t in (X, W, dY, bias))
+    oY, oXp = o_rmm.forward(X64, W64, b64, k, kind, seed, offset)
+    odX, odW, odb = o_rmm.backward(dY64, W64, synth.to_f64(Xp0), kind, seed, offset)
+    assert rel(synth.to_f64(Y0), oY) <= 1e-2 and rel(synth.to_f64(Xp0), oXp) <= 1e-2
+    assert rel(synth.to_f64(dX0), odX) <= 1e-2 and rel(synth.to_f64(dW0), odW) <= 1e-2
+    assert rel(synth.to_f64(db0), odb) <= 1e-2
+    # a second call draws another sketch
+    lin(Xd.detach())
+    assert lin.last_state == (77, (3 << 32) | 1)
+
+
+def test_weight_gradient_is_unbiased_over_calls():
+    """Mean of dW over many forward/backward calls approaches the exact X-based gradient
+    (Section 2.1: E[S S^T] = I); a single call is far from it at this k."""
+    n, d_in, d_out, k = 512, 64, 48, 64
+    X, W, dY = synth.layer_inputs(n, d_in, d_out, "f32", (61, 62, 63))
+    lin = rmm.RMMLinear(d_in, d_out, bias=False, k=k, seed=5, dtype=torch.float32)
+    with torch.no_grad():
+        lin.weight.copy_(W.to(DEV))
+    Xd, dYd = X.to(DEV), dY.to(DEV)
+    exact = synth.to_f64(dY).T @ synth.to_f64(X)
+    calls, acc, first = 400, np.zeros_like(exact), None
+    for _ in range(calls):
+        lin.weight.grad = None
+        lin(Xd).backward(dYd)
+        g = synth.to_f64(lin.weight.grad)
+        first = g if first is None else first
+        acc += g
+    err_mean, err_one = rel(acc / calls, exact), rel(first, exact)
+    print("relative error: one call %.3f, mean of %d calls %.3f" % (err_one, calls, err_mean), flush=True)
+    assert err_one > 5 * err_mean and err_mean < 2.5 * err_one / np.sqrt(calls)
