@@ -111,6 +111,14 @@ int rmm_backward(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void
                  const void *X_proj, void *dX, void *dW, void *dbias, void *ws, size_t ws_bytes,
                  void *stream);
 
+/* rmm_backward for gradient accumulation over micro-batches: dW (and dbias, if given) must
+ * hold valid values on entry and receive old value + this call's estimate (Algorithm 1,
+ * Backward, applied to a sum of losses; the sum is formed in fp32 and rounded once to the
+ * output dtype).  dX is overwritten as in rmm_backward.  Same arguments and errors. */
+int rmm_backward_accumulate(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *dY, const void *W,
+                            const void *X_proj, void *dX, void *dW, void *dbias, void *ws, size_t ws_bytes,
+                            void *stream);
+
 /* Stages of the two passes, for the profiled variants below. */
 typedef enum {
     RMM_STAGE_NONE = -1,

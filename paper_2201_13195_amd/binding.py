@@ -61,6 +61,8 @@ def load_library():
     L.rmm_backward.argtypes = [ctypes.POINTER(_Desc), _State, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.rmm_forward_profiled.restype = ci
     L.rmm_forward_profiled.argtypes = L.rmm_forward.argtypes + [ci, vp, vp]
+    L.rmm_backward_accumulate.restype = ci
+    L.rmm_backward_accumulate.argtypes = L.rmm_backward.argtypes
     L.rmm_backward_profiled.restype = ci
     L.rmm_backward_profiled.argtypes = L.rmm_backward.argtypes + [ci, vp, vp]
     L.rmm_debug_philox.restype = ci
@@ -169,8 +171,11 @@ def rmm_forward(X, W, bias, k, kind, seed, offset, Y=None, X_proj=None, ws=None,
 
 
 def rmm_backward(dY, W, X_proj, kind, seed, offset, need_dX=True, need_dbias=False, dX=None, dW=None, dbias=None,
-                 ws=None, profile=None):
-    """Algorithm 1 backward with the forward call's state.  Returns (dX, dW, dbias)."""
+                 ws=None, profile=None, accumulate=False):
+    """Algorithm 1 backward with the forward call's state.  Returns (dX, dW, dbias).  With
+    `accumulate` the given dW (and dbias) are added to instead of overwritten."""
+    if accumulate and (dW is None or (need_dbias and dbias is None) or profile is not None):
+        raise ValueError("accumulate needs existing dW / dbias tensors and no profile")
     n, d_out = dY.shape
     k, d_in = X_proj.shape
     if need_dX and dX is None:
@@ -182,13 +187,14 @@ def rmm_backward(dY, W, X_proj, kind, seed, offset, need_dX=True, need_dbias=Fal
     desc = _desc(n, d_in, d_out, k, dY.dtype, kind)
     need = rmm_workspace_bytes(n, d_in, d_out, k, dY.dtype, kind, OP_BACKWARD)
     ws, wsp, wsb = _workspace(ws, need, dY.device)
-    rc = load_library().rmm_backward_profiled(ctypes.byref(desc), _State(seed, offset), _ptr(dY, "dY"),
-                                              _ptr(W, "W", dY.dtype, (d_out, d_in)),
-                                              _ptr(X_proj, "X_proj", dY.dtype, (k, d_in)),
-                                              _ptr(dX, "dX", dY.dtype, (n, d_in), optional=True),
-                                              _ptr(dW, "dW", dY.dtype, (d_out, d_in)),
-                                              _ptr(dbias, "dbias", dY.dtype, (d_out,), optional=True),
-                                              wsp, wsb, _stream(dY), *_event_args(profile))
+    args = (ctypes.byref(desc), _State(seed, offset), _ptr(dY, "dY"), _ptr(W, "W", dY.dtype, (d_out, d_in)),
+            _ptr(X_proj, "X_proj", dY.dtype, (k, d_in)), _ptr(dX, "dX", dY.dtype, (n, d_in), optional=True),
+            _ptr(dW, "dW", dY.dtype, (d_out, d_in)), _ptr(dbias, "dbias", dY.dtype, (d_out,), optional=True),
+            wsp, wsb, _stream(dY))
+    if accumulate:
+        rc = load_library().rmm_backward_accumulate(*args)
+    else:
+        rc = load_library().rmm_backward_profiled(*args, *_event_args(profile))
     if rc != 0:
         raise RmmError(rc, "rmm_backward")
     return dX, dW, dbias

@@ -104,7 +104,8 @@ int forward_impl(const rmm_layer_desc_t *d, SketchState st, const void *X, const
 
 template <typename T>
 int backward_impl(const rmm_layer_desc_t *d, SketchState st, const void *dY, const void *W, const void *X_proj,
-                  void *dX, void *dW, void *dbias, void *ws, hipStream_t stream, const StageEvents &ev) {
+                  void *dX, void *dW, void *dbias, void *ws, hipStream_t stream, const StageEvents &ev,
+                  bool accumulate) {
     hipError_t e;
     const bool mfma = use_mfma(d);
     if (dX != nullptr) {  // dX = dY W: B(kk, c) = W[kk][c]
@@ -125,14 +126,14 @@ int backward_impl(const rmm_layer_desc_t *d, SketchState st, const void *dY, con
     {   // dW = G^T X_proj: A(r, kk) = G[kk][r], B(kk, c) = X_proj[kk][c]
         StageScope scope(ev, RMM_STAGE_BWD_DW, stream);
         e = mfma ? launch_dw_bf16((const bf16_t *)G, (const bf16_t *)X_proj, (bf16_t *)dW, d->k, d->d_in, d->d_out,
-                                  stream)
+                                  stream, accumulate)
                  : launch_gemm_plain<T, T>(G, 1, d->d_out, (const T *)X_proj, d->d_in, 1, (T *)dW, d->d_in,
-                                           (const T *)nullptr, d->d_out, d->d_in, d->k, 1.0f, stream);
+                                           (const T *)nullptr, d->d_out, d->d_in, d->k, 1.0f, stream, accumulate);
         if (e != hipSuccess) return RMM_ERR_LAUNCH;
     }
     if (dbias != nullptr) {
         StageScope scope(ev, RMM_STAGE_BWD_DBIAS, stream);
-        e = launch_colsum<T>((const T *)dY, (T *)dbias, d->n, d->d_out, stream);
+        e = launch_colsum<T>((const T *)dY, (T *)dbias, d->n, d->d_out, stream, accumulate);
         if (e != hipSuccess) return RMM_ERR_LAUNCH;
     }
     return RMM_OK;
@@ -219,9 +220,9 @@ int rmm_forward(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void 
                                 nullptr);
 }
 
-int rmm_backward_profiled(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *dY, const void *W,
-                          const void *X_proj, void *dX, void *dW, void *dbias, void *ws, size_t ws_bytes,
-                          void *stream, int stage, void *ev_begin, void *ev_end) {
+static int backward_checked(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *dY, const void *W,
+                            const void *X_proj, void *dX, void *dW, void *dbias, void *ws, size_t ws_bytes,
+                            void *stream, int stage, void *ev_begin, void *ev_end, bool accumulate) {
     if (!desc_ok(desc) || dY == nullptr || W == nullptr || X_proj == nullptr || dW == nullptr)
         return RMM_ERR_INVALID_ARG;
     if (!aligned16(dY) || !aligned16(W) || !aligned16(X_proj) || !aligned16(dX) || !aligned16(dW) || !aligned16(ws))
@@ -235,14 +236,29 @@ int rmm_backward_profiled(const rmm_layer_desc_t *desc, rmm_rng_state_t state, c
     ev.stage = stage;
     ev.begin = (hipEvent_t)ev_begin;
     ev.end = (hipEvent_t)ev_end;
-    return desc->dtype == RMM_DTYPE_BF16 ? backward_impl<bf16_t>(desc, st, dY, W, X_proj, dX, dW, dbias, ws, s, ev)
-                                         : backward_impl<float>(desc, st, dY, W, X_proj, dX, dW, dbias, ws, s, ev);
+    return desc->dtype == RMM_DTYPE_BF16
+               ? backward_impl<bf16_t>(desc, st, dY, W, X_proj, dX, dW, dbias, ws, s, ev, accumulate)
+               : backward_impl<float>(desc, st, dY, W, X_proj, dX, dW, dbias, ws, s, ev, accumulate);
+}
+
+int rmm_backward_profiled(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *dY, const void *W,
+                          const void *X_proj, void *dX, void *dW, void *dbias, void *ws, size_t ws_bytes,
+                          void *stream, int stage, void *ev_begin, void *ev_end) {
+    return backward_checked(desc, state, dY, W, X_proj, dX, dW, dbias, ws, ws_bytes, stream, stage, ev_begin, ev_end,
+                            false);
 }
 
 int rmm_backward(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *dY, const void *W,
                  const void *X_proj, void *dX, void *dW, void *dbias, void *ws, size_t ws_bytes, void *stream) {
-    return rmm_backward_profiled(desc, state, dY, W, X_proj, dX, dW, dbias, ws, ws_bytes, stream, RMM_STAGE_NONE,
-                                 nullptr, nullptr);
+    return backward_checked(desc, state, dY, W, X_proj, dX, dW, dbias, ws, ws_bytes, stream, RMM_STAGE_NONE, nullptr,
+                            nullptr, false);
+}
+
+int rmm_backward_accumulate(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *dY, const void *W,
+                            const void *X_proj, void *dX, void *dW, void *dbias, void *ws, size_t ws_bytes,
+                            void *stream) {
+    return backward_checked(desc, state, dY, W, X_proj, dX, dW, dbias, ws, ws_bytes, stream, RMM_STAGE_NONE, nullptr,
+                            nullptr, true);
 }
 
 int rmm_debug_philox(rmm_rng_state_t state, uint32_t c0, uint32_t c1, int64_t ncalls, uint32_t *out, void *stream) {

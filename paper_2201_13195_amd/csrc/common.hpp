@@ -38,19 +38,19 @@ __device__ __forceinline__ void store_f32<bf16_t>(bf16_t *p, float v) { *p = f32
 // ---------------------------------------------------------------------------
 
 // Plain LDS-tiled fp32-FMA kernels: the fp32 data path, and a slow bf16 one.
-//   C[m x n] = alpha * A * B (+ bias[n] per row), A(m,kk) at A[m*sam + kk*sak],
-//   B(kk,n) at B[kk*sbk + n*sbn], C row-major with leading dimension ldc.
+//   C[m x n] = alpha * A * B (+ bias[n] per row) (+ the old C if `accumulate`), A(m,kk) at
+//   A[m*sam + kk*sak], B(kk,n) at B[kk*sbk + n*sbn], C row-major with leading dimension ldc.
 template <typename Tin, typename Tout>
 hipError_t launch_gemm_plain(const Tin *A, int64_t sam, int64_t sak, const Tin *B, int64_t sbk, int64_t sbn,
                              Tout *C, int64_t ldc, const Tin *bias, int64_t m, int64_t n, int64_t kk, float alpha,
-                             hipStream_t stream);
+                             hipStream_t stream, bool accumulate = false);
 //   out[k x d] = alpha * P^T A with P the unscaled sketch (n x k) of `st`.
 template <typename Tin, typename Tout>
 hipError_t launch_sketch_plain(const Tin *A, Tout *out, int64_t n, int64_t d, int64_t k, int kind, SketchState st,
                                float alpha, hipStream_t stream);
-//   out[d] = column sums of A[n x d].
+//   out[d] = column sums of A[n x d] (+ the old out if `accumulate`).
 template <typename T>
-hipError_t launch_colsum(const T *A, T *out, int64_t n, int64_t d, hipStream_t stream);
+hipError_t launch_colsum(const T *A, T *out, int64_t n, int64_t d, hipStream_t stream, bool accumulate = false);
 
 // bf16 MFMA path (mfma.hip).  Usable when mfma_shape_ok(); `ws` for the sketch
 // must hold sketch_workspace_bf16() bytes (fp32 partial sums of the token slices).
@@ -62,7 +62,7 @@ hipError_t launch_linear_nt_bf16(const bf16_t *X, const bf16_t *W, const bf16_t 
 hipError_t launch_linear_nn_bf16(const bf16_t *dY, const bf16_t *W, bf16_t *dX, int64_t n, int64_t d_in,
                                  int64_t d_out, hipStream_t stream);
 hipError_t launch_dw_bf16(const bf16_t *G, const bf16_t *X_proj, bf16_t *dW, int64_t k, int64_t d_in, int64_t d_out,
-                          hipStream_t stream);
+                          hipStream_t stream, bool accumulate = false);
 size_t sketch_workspace_bf16(int64_t n, int64_t d, int64_t k);
 hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d, int64_t k, int kind, SketchState st,
                               void *ws, hipStream_t stream, hipEvent_t ev_begin = nullptr,

@@ -32,7 +32,7 @@ struct SketchSrc {
 template <typename ASrc, typename BSrc, typename Tout, typename Tbias>
 __global__ void __launch_bounds__(256) gemm_plain_kernel(ASrc A, BSrc B, Tout *__restrict__ C, int64_t ldc,
                                                          const Tbias *__restrict__ bias, int64_t m, int64_t n,
-                                                         int64_t kk, float alpha) {
+                                                         int64_t kk, float alpha, bool accumulate) {
     __shared__ float As[TK][TM + 4];
     __shared__ float Bs[TK][TN + 4];
     const int tid = threadIdx.x;
@@ -75,6 +75,7 @@ __global__ void __launch_bounds__(256) gemm_plain_kernel(ASrc A, BSrc B, Tout *_
             if (gn >= n) continue;
             float r = alpha * acc[u][v];
             if (bias != nullptr) r += load_f32<Tbias>(bias + gn);
+            if (accumulate) r += load_f32<Tout>(C + gm * ldc + gn);
             store_f32<Tout>(C + gm * ldc + gn, r);
         }
     }
@@ -83,7 +84,7 @@ __global__ void __launch_bounds__(256) gemm_plain_kernel(ASrc A, BSrc B, Tout *_
 // out[c] = sum_r A[r][c]; 64 columns per work-group, 4 row lanes per column.
 template <typename T>
 __global__ void __launch_bounds__(256) colsum_kernel(const T *__restrict__ A, T *__restrict__ out, int64_t n,
-                                                     int64_t d) {
+                                                     int64_t d, bool accumulate) {
     __shared__ float part[4][64];
     const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
     const int64_t c = (int64_t)blockIdx.x * 64 + cl;
@@ -92,7 +93,11 @@ __global__ void __launch_bounds__(256) colsum_kernel(const T *__restrict__ A, T 
         for (int64_t r = rl; r < n; r += 4) s += load_f32<T>(A + r * d + c);
     part[rl][cl] = s;
     __syncthreads();
-    if (rl == 0 && c < d) store_f32<T>(out + c, (part[0][cl] + part[1][cl]) + (part[2][cl] + part[3][cl]));
+    if (rl == 0 && c < d) {
+        float r = (part[0][cl] + part[1][cl]) + (part[2][cl] + part[3][cl]);
+        if (accumulate) r += load_f32<T>(out + c);
+        store_f32<T>(out + c, r);
+    }
 }
 
 __global__ void debug_philox_kernel(SketchState st, uint32_t c0, uint32_t c1, int64_t ncalls,
@@ -117,11 +122,11 @@ __global__ void debug_sketch_tile_kernel(int kind, SketchState st, int64_t i0, i
 template <typename Tin, typename Tout>
 hipError_t launch_gemm_plain(const Tin *A, int64_t sam, int64_t sak, const Tin *B, int64_t sbk, int64_t sbn,
                              Tout *C, int64_t ldc, const Tin *bias, int64_t m, int64_t n, int64_t kk, float alpha,
-                             hipStream_t stream) {
+                             hipStream_t stream, bool accumulate) {
     MemSrc<Tin> a{A, sam, sak}, b{B, sbk, sbn};
     dim3 grid((unsigned)((n + TN - 1) / TN), (unsigned)((m + TM - 1) / TM));
     gemm_plain_kernel<MemSrc<Tin>, MemSrc<Tin>, Tout, Tin><<<grid, 256, 0, stream>>>(a, b, C, ldc, bias, m, n, kk,
-                                                                                      alpha);
+                                                                                      alpha, accumulate);
     return hipGetLastError();
 }
 
@@ -132,13 +137,13 @@ hipError_t launch_sketch_plain(const Tin *A, Tout *out, int64_t n, int64_t d, in
     MemSrc<Tin> b{A, d, 1};
     dim3 grid((unsigned)((d + TN - 1) / TN), (unsigned)((k + TM - 1) / TM));
     gemm_plain_kernel<SketchSrc, MemSrc<Tin>, Tout, Tin><<<grid, 256, 0, stream>>>(a, b, out, d, (const Tin *)nullptr,
-                                                                                    k, d, n, alpha);
+                                                                                    k, d, n, alpha, false);
     return hipGetLastError();
 }
 
 template <typename T>
-hipError_t launch_colsum(const T *A, T *out, int64_t n, int64_t d, hipStream_t stream) {
-    colsum_kernel<T><<<(unsigned)((d + 63) / 64), 256, 0, stream>>>(A, out, n, d);
+hipError_t launch_colsum(const T *A, T *out, int64_t n, int64_t d, hipStream_t stream, bool accumulate) {
+    colsum_kernel<T><<<(unsigned)((d + 63) / 64), 256, 0, stream>>>(A, out, n, d, accumulate);
     return hipGetLastError();
 }
 
@@ -158,13 +163,13 @@ hipError_t launch_debug_sketch_tile(int kind, SketchState st, int64_t i0, int64_
 #define RMM_INSTANTIATE(Tin, Tout)                                                                              \
     template hipError_t launch_gemm_plain<Tin, Tout>(const Tin *, int64_t, int64_t, const Tin *, int64_t,       \
                                                      int64_t, Tout *, int64_t, const Tin *, int64_t, int64_t,   \
-                                                     int64_t, float, hipStream_t);                              \
+                                                     int64_t, float, hipStream_t, bool);                        \
     template hipError_t launch_sketch_plain<Tin, Tout>(const Tin *, Tout *, int64_t, int64_t, int64_t, int,     \
                                                        SketchState, float, hipStream_t);
 RMM_INSTANTIATE(float, float)
 RMM_INSTANTIATE(bf16_t, bf16_t)
 #undef RMM_INSTANTIATE
-template hipError_t launch_colsum<float>(const float *, float *, int64_t, int64_t, hipStream_t);
-template hipError_t launch_colsum<bf16_t>(const bf16_t *, bf16_t *, int64_t, int64_t, hipStream_t);
+template hipError_t launch_colsum<float>(const float *, float *, int64_t, int64_t, hipStream_t, bool);
+template hipError_t launch_colsum<bf16_t>(const bf16_t *, bf16_t *, int64_t, int64_t, hipStream_t, bool);
 
 }  // namespace rmm

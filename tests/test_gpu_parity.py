@@ -252,3 +252,34 @@ def test_profiled_entry_points_time_one_stage_and_change_nothing():
     Xp2 = rmm.rmm_sketch(Xd, k, kind, 9, 1, events=(a, b))
     torch.cuda.synchronize()
     assert torch.equal(Xp2, Xp0) and 0.0 < a.elapsed_time(b) < 50.0
+
+
+@pytest.mark.parametrize("dtype,shape", [("f32", (333, 200, 136, 77)), ("bf16", (333, 200, 136, 77)),
+                                         ("bf16", (700, 264, 520, 96)), ("bf16", (300, 1544, 1608, 1550))])
+def test_backward_accumulate_over_two_micro_batches(dtype, shape):
+    """Gradient accumulation: the second micro-batch's backward adds its dW and dbias to the
+    first one's (plain sum of two Algorithm 1 backward results), dX is overwritten."""
+    n, d_in, d_out, k = shape
+    kind = rmm.GAUSSIAN
+    X1, W, dY1 = synth.layer_inputs(n, d_in, d_out, dtype, (71, 72, 73), w_std=1.0 / math.sqrt(d_in))
+    X2, _, dY2 = synth.layer_inputs(n, d_in, d_out, dtype, (74, 72, 75), w_std=1.0 / math.sqrt(d_in))
+    Wd = W.to(DEV)
+    _, Xp1 = rmm.rmm_forward(X1.to(DEV), Wd, None, k, kind, 9, 100)
+    _, Xp2 = rmm.rmm_forward(X2.to(DEV), Wd, None, k, kind, 9, 101)
+    dX1, dW, db = rmm.rmm_backward(dY1.to(DEV), Wd, Xp1, kind, 9, 100, need_dbias=True)
+    dW_first, db_first = synth.to_f64(dW), synth.to_f64(db)
+    dX2, dW_b, db_b = rmm.rmm_backward(dY2.to(DEV), Wd, Xp2, kind, 9, 101, need_dbias=True, dW=dW, dbias=db,
+                                       accumulate=True)
+    assert dW_b is dW and db_b is db
+    W64 = synth.to_f64(W)
+    odX1, odW1, odb1 = o_rmm.backward(synth.to_f64(dY1), W64, synth.to_f64(Xp1), kind, 9, 100)
+    odX2, odW2, odb2 = o_rmm.backward(synth.to_f64(dY2), W64, synth.to_f64(Xp2), kind, 9, 101)
+    tol = TOL[dtype]
+    errs = {"dW_sum": rel_fro(dW, odW1 + odW2), "dW_step": rel_fro(dW, dW_first + odW2),
+            "db_sum": rel_fro(db, odb1 + odb2), "db_step": rel_fro(db, db_first + odb2),
+            "dX1": rel_fro(dX1, odX1), "dX2": rel_fro(dX2, odX2)}
+    print(shape, dtype, {k_: "%.2e" % v for k_, v in errs.items()}, flush=True)
+    for name, e in errs.items():
+        assert e <= tol, (name, e)
+    # the accumulated result is not just the second estimate
+    assert rel_fro(dW, odW2) > 0.3
