@@ -128,6 +128,27 @@ def sketch_roofline(torch, rmm, binding, dev, kind, kind_name, n=16384, d=4096, 
             "avg_call_ms": cms, "algorithmic_bytes_per_launch": nbytes}
 
 
+def variance_monitor(torch, rmm, X, dY, k, kind, reps=30):
+    """rmm_variance_stats (Section 2.3 monitors) on the workload's X and dY: one HBM pass for the
+    row norms, the X^T dY product with a squared-norm epilogue, a one-wave finalize."""
+    n, d_in = X.shape
+    d_out = dY.shape[1]
+    out = torch.empty((8,), dtype=torch.float64, device=X.device)
+    ws = torch.empty(rmm.rmm_workspace_bytes(n, d_in, d_out, k, X.dtype, kind, 3), dtype=torch.uint8, device=X.device)
+    for _ in range(3):
+        rmm.rmm_variance_stats(X, dY, k, kind, out=out, ws=ws)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in evs:
+        a.record()
+        rmm.rmm_variance_stats(X, dY, k, kind, out=out, ws=ws)
+        b.record()
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in evs)[reps // 2]
+    fl = 2 * n * d_in * d_out
+    return {"avg_call_ms": ms, "flops_per_call": fl, "tflops": fl / (ms * 1e-3) / 1e12,
+            "alpha": float(out[6]), "d2_rmm_over_d2_sgd": float(out[5] / out[4])}
+
+
 def bench_stack(args, torch, rmm, synth, dev, kind):
     """The 24-block stack of RoBERTa-large-shaped layers (144 layers, N = 16384, k = 1638): a step
     is the forward sweep that keeps only X_proj + state per layer, then the backward sweep in
@@ -198,6 +219,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sketch-roofline", action="store_true",
                     help="skip the small-k rmm_sketch measurement against the HBM roofline")
+    ap.add_argument("--no-variance-monitor", action="store_true",
+                    help="skip timing rmm_variance_stats on the workload's X and dY")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="only run a plain copy of this many MiB (counter calibration) and exit")
     args = ap.parse_args()
@@ -322,6 +345,8 @@ def main():
     }
     if not args.no_sketch_roofline:
         out["sketch_hbm_roofline"] = sketch_roofline(torch, rmm, binding, dev, kind, args.kind)
+    if not args.no_variance_monitor and cfg["dtype"] == "bf16":
+        out["variance_monitor"] = variance_monitor(torch, rmm, sets[0]["X"], sets[0]["dY"], k, kind)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, kind)
     print(json.dumps(out))

@@ -62,7 +62,7 @@ typedef enum {
 
 typedef enum { RMM_DTYPE_F32 = 0, RMM_DTYPE_BF16 = 1 } rmm_dtype_t;
 typedef enum { RMM_SKETCH_GAUSSIAN = 0, RMM_SKETCH_RADEMACHER = 1 } rmm_sketch_kind_t;
-typedef enum { RMM_OP_FORWARD = 0, RMM_OP_BACKWARD = 1, RMM_OP_SKETCH = 2 } rmm_op_t;
+typedef enum { RMM_OP_FORWARD = 0, RMM_OP_BACKWARD = 1, RMM_OP_SKETCH = 2, RMM_OP_VARIANCE = 3 } rmm_op_t;
 
 /* The "PRNG state" saved between forward and backward (Algorithm 1): 16 bytes. */
 typedef struct {
@@ -118,6 +118,21 @@ int rmm_backward(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void
 int rmm_backward_accumulate(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *dY, const void *W,
                             const void *X_proj, void *dX, void *dW, void *dbias, void *ws, size_t ws_bytes,
                             void *stream);
+
+/* Variance monitors of Section 2.3 for one layer call, from X[n x d_in] and dY[n x d_out]
+ * (device, read only; Y of the lemmas is dY).  out: 8 doubles on the device, 8-byte aligned:
+ *   out[0] = |X|_F^2            out[1] = |dY|_F^2
+ *   out[2] = sum_k |x_k|^2 |y_k|^2 over the token rows        out[3] = |X^T dY|_F^2
+ *   out[4] = D^2_SGD = n/(n-1) out[2] - out[3]/(n-1)           (Lemma 2.1; 0 for n = 1)
+ *   out[5] = D^2_RMM for sketch size desc->k and kind desc->kind: (out[0] out[1] + out[3]) / k
+ *            for Gaussian S, less 2 out[2] / k for Rademacher S (Lemma 2.2 with the sign that
+ *            the fourth moment of the sketch entries gives to the |X^T dY|^2 term)
+ *   out[6] = alpha = out[3] / (out[0] out[1])                  (Theorem 2.3)
+ *   out[7] = (out[0] out[1] - out[3]) / k                      (Lemma 2.2 as printed)
+ * Sums are taken in fixed order (bit-reproducible).  Workspace: rmm_workspace_bytes(desc,
+ * RMM_OP_VARIANCE), never zero. */
+int rmm_variance_stats(const rmm_layer_desc_t *desc, const void *X, const void *dY, double *out, void *ws,
+                       size_t ws_bytes, void *stream);
 
 /* Stages of the two passes, for the profiled variants below. */
 typedef enum {

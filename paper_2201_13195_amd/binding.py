@@ -8,7 +8,7 @@ import torch
 
 GAUSSIAN = 0
 RADEMACHER = 1
-OP_FORWARD, OP_BACKWARD, OP_SKETCH = 0, 1, 2
+OP_FORWARD, OP_BACKWARD, OP_SKETCH, OP_VARIANCE = 0, 1, 2, 3
 _DTYPES = {torch.float32: 0, torch.bfloat16: 1}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -61,6 +61,8 @@ def load_library():
     L.rmm_backward.argtypes = [ctypes.POINTER(_Desc), _State, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.rmm_forward_profiled.restype = ci
     L.rmm_forward_profiled.argtypes = L.rmm_forward.argtypes + [ci, vp, vp]
+    L.rmm_variance_stats.restype = ci
+    L.rmm_variance_stats.argtypes = [ctypes.POINTER(_Desc), vp, vp, vp, vp, sz, vp]
     L.rmm_backward_accumulate.restype = ci
     L.rmm_backward_accumulate.argtypes = L.rmm_backward.argtypes
     L.rmm_backward_profiled.restype = ci
@@ -132,6 +134,25 @@ def rmm_sketch(A, k, kind, seed, offset, out=None, ws=None, events=None):
                                             _ptr(out, "out", A.dtype, (k, d)), wsp, wsb, _stream(A), evb, eve)
     if rc != 0:
         raise RmmError(rc, "rmm_sketch")
+    return out
+
+
+VARIANCE_FIELDS = ("x_fro2", "y_fro2", "rows", "xty_fro2", "d2_sgd", "d2_rmm", "alpha", "d2_rmm_printed")
+
+
+def rmm_variance_stats(X, dY, k, kind, out=None, ws=None):
+    """Variance monitors of Section 2.3.  Returns a device tensor of 8 doubles (VARIANCE_FIELDS)."""
+    n, d_in = X.shape
+    d_out = dY.shape[1]
+    if out is None:
+        out = torch.empty((8,), dtype=torch.float64, device=X.device)
+    desc = _desc(n, d_in, d_out, k, X.dtype, kind)
+    need = rmm_workspace_bytes(n, d_in, d_out, k, X.dtype, kind, OP_VARIANCE)
+    ws, wsp, wsb = _workspace(ws, need, X.device)
+    rc = load_library().rmm_variance_stats(ctypes.byref(desc), _ptr(X, "X"), _ptr(dY, "dY", X.dtype, (n, d_out)),
+                                           _ptr(out, "out", torch.float64, (8,)), wsp, wsb, _stream(X))
+    if rc != 0:
+        raise RmmError(rc, "rmm_variance_stats")
     return out
 
 

@@ -46,6 +46,17 @@ size_t ws_backward(const rmm_layer_desc_t *d) {
     return g_bytes(d) + (use_mfma(d) ? round_up(sketch_workspace_bf16(d->n, d->d_out, d->k), 256) : 0);
 }
 
+// variance monitors: per-block partials (doubles), then, off the MFMA path, X^T dY in fp32.
+int var_xty_partials(const rmm_layer_desc_t *d) {
+    return use_mfma(d) ? xty_sumsq_tiles(d->n, d->d_in, d->d_out) : sumsq_blocks(d->d_in * d->d_out);
+}
+size_t var_partial_bytes(const rmm_layer_desc_t *d) {
+    return round_up(((size_t)3 * row_norm_blocks(d->n) + (size_t)var_xty_partials(d)) * sizeof(double), 256);
+}
+size_t ws_variance(const rmm_layer_desc_t *d) {
+    return var_partial_bytes(d) + (use_mfma(d) ? 0 : round_up((size_t)d->d_in * d->d_out * sizeof(float), 256));
+}
+
 int from_hip(hipError_t e) { return e == hipSuccess ? RMM_OK : RMM_ERR_LAUNCH; }
 
 // Optional pair of caller-owned events bracketing one stage of a pass.
@@ -165,6 +176,7 @@ size_t rmm_workspace_bytes(const rmm_layer_desc_t *desc, int op) {
         case RMM_OP_FORWARD: return ws_forward(&d);
         case RMM_OP_BACKWARD: return ws_backward(&d);
         case RMM_OP_SKETCH: return ws_sketch(&d);
+        case RMM_OP_VARIANCE: return ws_variance(&d);
         default: return 0;
     }
 }
@@ -259,6 +271,40 @@ int rmm_backward_accumulate(const rmm_layer_desc_t *desc, rmm_rng_state_t state,
                             void *stream) {
     return backward_checked(desc, state, dY, W, X_proj, dX, dW, dbias, ws, ws_bytes, stream, RMM_STAGE_NONE, nullptr,
                             nullptr, true);
+}
+
+int rmm_variance_stats(const rmm_layer_desc_t *desc, const void *X, const void *dY, double *out, void *ws,
+                       size_t ws_bytes, void *stream) {
+    if (!desc_ok(desc) || X == nullptr || dY == nullptr || out == nullptr) return RMM_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(dY) || !aligned16(ws) || ((uintptr_t)out & 7u) != 0) return RMM_ERR_INVALID_ARG;
+    if (ws == nullptr || ws_bytes < ws_variance(desc)) return RMM_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const int nb = row_norm_blocks(desc->n), nt = var_xty_partials(desc);
+    double *rows = (double *)ws, *xty = rows + 3 * (size_t)nb;
+    hipError_t e;
+    if (desc->dtype == RMM_DTYPE_BF16) {
+        e = launch_row_norms<bf16_t>((const bf16_t *)X, (const bf16_t *)dY, desc->n, desc->d_in, desc->d_out, rows, s);
+        if (e != hipSuccess) return RMM_ERR_LAUNCH;
+        if (use_mfma(desc)) {
+            e = launch_xty_sumsq_bf16((const bf16_t *)X, (const bf16_t *)dY, xty, desc->n, desc->d_in, desc->d_out, s);
+        } else {
+            float *P = (float *)((char *)ws + var_partial_bytes(desc));  // P(i, j) = sum_t X[t][i] dY[t][j]
+            e = launch_gemm_plain<bf16_t, float>((const bf16_t *)X, 1, desc->d_in, (const bf16_t *)dY, desc->d_out, 1, P,
+                                                 desc->d_out, (const bf16_t *)nullptr, desc->d_in, desc->d_out,
+                                                 desc->n, 1.0f, s);
+            if (e == hipSuccess) e = launch_sumsq(P, desc->d_in * desc->d_out, xty, s);
+        }
+    } else {
+        e = launch_row_norms<float>((const float *)X, (const float *)dY, desc->n, desc->d_in, desc->d_out, rows, s);
+        if (e != hipSuccess) return RMM_ERR_LAUNCH;
+        float *P = (float *)((char *)ws + var_partial_bytes(desc));
+        e = launch_gemm_plain<float, float>((const float *)X, 1, desc->d_in, (const float *)dY, desc->d_out, 1, P,
+                                            desc->d_out, (const float *)nullptr, desc->d_in, desc->d_out, desc->n,
+                                            1.0f, s);
+        if (e == hipSuccess) e = launch_sumsq(P, desc->d_in * desc->d_out, xty, s);
+    }
+    if (e != hipSuccess) return RMM_ERR_LAUNCH;
+    return from_hip(launch_variance_finalize(rows, nb, xty, nt, desc->n, desc->k, desc->kind, out, s));
 }
 
 int rmm_debug_philox(rmm_rng_state_t state, uint32_t c0, uint32_t c1, int64_t ncalls, uint32_t *out, void *stream) {

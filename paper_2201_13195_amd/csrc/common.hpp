@@ -68,6 +68,22 @@ hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d
                               void *ws, hipStream_t stream, hipEvent_t ev_begin = nullptr,
                               hipEvent_t ev_end = nullptr);
 
+// Variance monitors (variance.hip, and the squared-norm epilogue of the MFMA kernel).
+//   part[3*b..] = per-block (sum |x_k|^2, sum |y_k|^2, sum |x_k|^2 |y_k|^2); row_norm_blocks(n) blocks.
+int row_norm_blocks(int64_t n);
+template <typename T>
+hipError_t launch_row_norms(const T *X, const T *Y, int64_t n, int64_t d_in, int64_t d_out, double *part,
+                            hipStream_t stream);
+//   part[b] = per-block sum of squares of an fp32 buffer; sumsq_blocks(elems) blocks.
+int sumsq_blocks(int64_t elems);
+hipError_t launch_sumsq(const float *A, int64_t elems, double *part, hipStream_t stream);
+//   part[t] = sum of squares of tile t of X^T dY (d_in x d_out), bf16 MFMA path; xty_sumsq_tiles() tiles.
+int xty_sumsq_tiles(int64_t n, int64_t d_in, int64_t d_out);
+hipError_t launch_xty_sumsq_bf16(const bf16_t *X, const bf16_t *dY, double *part, int64_t n, int64_t d_in,
+                                 int64_t d_out, hipStream_t stream);
+hipError_t launch_variance_finalize(const double *rows, int nb, const double *xty, int nt, int64_t n, int64_t k,
+                                    int kind, double *out, hipStream_t stream);
+
 hipError_t launch_debug_philox(SketchState st, uint32_t c0, uint32_t c1, int64_t ncalls, uint32_t *out,
                                hipStream_t stream);
 hipError_t launch_debug_sketch_tile(int kind, SketchState st, int64_t i0, int64_t j0, int64_t rows, int64_t cols,

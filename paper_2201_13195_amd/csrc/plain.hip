@@ -169,6 +169,9 @@ hipError_t launch_debug_sketch_tile(int kind, SketchState st, int64_t i0, int64_
 RMM_INSTANTIATE(float, float)
 RMM_INSTANTIATE(bf16_t, bf16_t)
 #undef RMM_INSTANTIATE
+template hipError_t launch_gemm_plain<bf16_t, float>(const bf16_t *, int64_t, int64_t, const bf16_t *, int64_t, int64_t,
+                                                     float *, int64_t, const bf16_t *, int64_t, int64_t, int64_t,
+                                                     float, hipStream_t, bool);
 template hipError_t launch_colsum<float>(const float *, float *, int64_t, int64_t, hipStream_t, bool);
 template hipError_t launch_colsum<bf16_t>(const bf16_t *, bf16_t *, int64_t, int64_t, hipStream_t, bool);
 
