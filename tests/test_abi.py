@@ -97,3 +97,28 @@ def test_product_package_does_not_touch_the_oracle():
             if f.endswith((".py", ".hip", ".hpp", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text, os.path.join(dirpath, f)
+
+
+def test_workspace_sizes_follow_the_documented_layout(lib):
+    """Host-side planning only: forward = the sketch of X; backward = G (k x d_out in the layer's
+    dtype, rounded to 256 bytes) + the sketch of dY; partial-sum slices never outnumber the
+    128-token blocks; the fp32 path needs no sketch partials; the variance op always needs some."""
+    bf16, f32 = torch.bfloat16, torch.float32
+    for n, d_in, d_out, k in [(4096, 768, 3072, 410), (16384, 1024, 4096, 1638), (16384, 4096, 1024, 32),
+                              (333, 200, 136, 77), (100, 8, 8, 3), (4100, 520, 264, 64), (1, 8, 8, 1)]:
+        fwd = rmm.rmm_workspace_bytes(n, d_in, d_out, k, bf16, 0, binding.OP_FORWARD)
+        bwd = rmm.rmm_workspace_bytes(n, d_in, d_out, k, bf16, 0, binding.OP_BACKWARD)
+        sk_x = rmm.rmm_workspace_bytes(n, d_in, d_in, k, bf16, 0, binding.OP_SKETCH)
+        sk_y = rmm.rmm_workspace_bytes(n, d_out, d_out, k, bf16, 0, binding.OP_SKETCH)
+        g = (k * d_out * 2 + 255) // 256 * 256
+        assert fwd == sk_x and bwd == g + sk_y, (n, d_in, d_out, k)
+        for sk, d in ((sk_x, d_in), (sk_y, d_out)):
+            assert sk % 256 == 0
+            slices = sk / (k * d * 4)
+            assert slices == 0 or 2 <= slices <= (n + 127) // 128 + 0.01
+        assert rmm.rmm_workspace_bytes(n, d_in, d_out, k, f32, 0, binding.OP_FORWARD) == 0
+        assert rmm.rmm_workspace_bytes(n, d_in, d_out, k, f32, 0, binding.OP_BACKWARD) == (k * d_out * 4 + 255) // 256 * 256
+        for dt in (bf16, f32):
+            assert rmm.rmm_workspace_bytes(n, d_in, d_out, k, dt, 1, binding.OP_VARIANCE) >= 256
+    # widths that are not multiples of 8 take the plain kernels: no partials
+    assert rmm.rmm_workspace_bytes(300, 67, 101, 9, bf16, 0, binding.OP_FORWARD) == 0
