@@ -72,3 +72,39 @@ def test_weight_gradient_is_unbiased_over_calls():
     err_mean, err_one = rel(acc / calls, exact), rel(first, exact)
     print("relative error: one call %.3f, mean of %d calls %.3f" % (err_one, calls, err_mean), flush=True)
     assert err_one > 5 * err_mean and err_mean < 2.5 * err_one / np.sqrt(calls)
+
+
+def test_two_layer_mlp_trains_with_sketched_weight_gradients():
+    """End to end through autograd: a GELU MLP of two RMM layers fits a random teacher with plain
+    SGD although every weight gradient is the sketched estimate (rho = 0.5), about as well as the
+    same MLP with exact gradients from the same start."""
+    torch.manual_seed(0)
+    n, d, h = 1024, 64, 128
+    X = torch.randn(n, d, device=DEV)
+    teacher = torch.nn.Sequential(torch.nn.Linear(d, h), torch.nn.GELU(), torch.nn.Linear(h, d)).to(DEV)
+    with torch.no_grad():
+        target = teacher(X)
+    W1 = torch.randn(h, d, device=DEV) / d ** 0.5
+    W2 = torch.randn(d, h, device=DEV) / h ** 0.5
+
+    def train(make):
+        l1, l2 = make(d, h, 0), make(h, d, 1)
+        with torch.no_grad():
+            l1.weight.copy_(W1), l2.weight.copy_(W2)
+            l1.bias.zero_(), l2.bias.zero_()
+        opt = torch.optim.SGD(list(l1.parameters()) + list(l2.parameters()), lr=0.1)
+        losses = []
+        for _ in range(200):
+            opt.zero_grad()
+            loss = torch.nn.functional.mse_loss(l2(torch.nn.functional.gelu(l1(X))), target)
+            loss.backward()
+            opt.step()
+            losses.append(float(loss.detach()))
+        return losses, (l1, l2)
+
+    exact, _ = train(lambda i, o, idx: torch.nn.Linear(i, o).to(DEV))
+    sketched, (l1, l2) = train(lambda i, o, idx: rmm.RMMLinear(i, o, rho=0.5, seed=1, layer_id=idx, dtype=torch.float32))
+    print("loss exact %.4f -> %.4f, sketched %.4f -> %.4f" % (exact[0], exact[-1], sketched[0], sketched[-1]), flush=True)
+    assert all(np.isfinite(sketched)) and abs(sketched[0] - exact[0]) < 1e-4 * exact[0]
+    assert sketched[-1] < 0.6 * sketched[0] and sketched[-1] < 1.5 * exact[-1]
+    assert l1.calls == 200 and l2.last_state == (1, (1 << 32) | 199)
