@@ -316,6 +316,14 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     dom_ms = sum(a.elapsed_time(b) for a, b in evs) / args.steps
+    # what an event pair with nothing between it measures on this stream (for comparing the
+    # event-bracketed duration with the profiler's kernel duration; not subtracted anywhere)
+    cal = new_events(50)
+    for a, b in cal:
+        a.record()
+        b.record()
+    torch.cuda.synchronize()
+    empty_pair_ms = sorted(a.elapsed_time(b) for a, b in cal)[len(cal) // 2]
 
     fl = stage_flops(n, d_in, d_out, k)
     by = stage_bytes(n, d_in, d_out, k, esize)
@@ -338,7 +346,8 @@ def main():
                    "saved_fraction": saved / (n * d_in * esize)},
         "roofline": {"bound": "mfma", "kernel": KERNEL_NAME[dominant], "stage": dominant, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": read_traffic(args.workload, dominant),
-                     "avg_launch_ms": dom_ms, "flops_per_launch": fl[dominant],
+                     "avg_launch_ms": dom_ms, "empty_event_pair_ms": empty_pair_ms,
+                     "flops_per_launch": fl[dominant],
                      "algorithmic_bytes_per_launch": by[dominant]},
         "stages_ms": stage_ms, "stage_kernel_ms": kernel_ms,
         "stages_tflops": {s: fl[s] / (stage_ms[s] * 1e-3) / 1e12 for s in STAGES},
