@@ -122,3 +122,26 @@ def test_workspace_sizes_follow_the_documented_layout(lib):
             assert rmm.rmm_workspace_bytes(n, d_in, d_out, k, dt, 1, binding.OP_VARIANCE) >= 256
     # widths that are not multiples of 8 take the plain kernels: no partials
     assert rmm.rmm_workspace_bytes(300, 67, 101, 9, bf16, 0, binding.OP_FORWARD) == 0
+
+
+def test_new_entry_points_validate_before_launching(lib):
+    D, S = binding._Desc, binding._State
+    st, good, fake = S(1, 2), D(64, 32, 32, 8, 0, 0), ctypes.c_void_p(0x1000)
+    lib.rmm_variance_stats.restype = ctypes.c_int
+    assert lib.rmm_variance_stats(None, fake, fake, fake, fake, 1 << 20, None) == -1
+    assert lib.rmm_variance_stats(ctypes.byref(good), None, fake, fake, fake, 1 << 20, None) == -1
+    assert lib.rmm_variance_stats(ctypes.byref(good), fake, fake, ctypes.c_void_p(0x1004), fake, 1 << 20, None) == -1
+    assert lib.rmm_variance_stats(ctypes.byref(good), fake, fake, fake, None, 0, None) == -3
+    assert lib.rmm_variance_stats(ctypes.byref(good), fake, fake, fake, fake, 8, None) == -3
+    assert lib.rmm_backward_accumulate(ctypes.byref(good), st, fake, fake, fake, fake, None, None, None, 0, None) == -1
+    assert lib.rmm_backward_accumulate(ctypes.byref(good), st, fake, fake, fake, fake, fake, None, None, 0, None) == -3
+    assert lib.rmm_sketch_profiled(0, 4, 4, 0, 0, st, fake, fake, None, 0, None, None, None) == -1
+
+
+def test_operands_of_two_gib_or_more_leave_the_mfma_path(lib):
+    """The MFMA kernels address operands with 32-bit buffer offsets; a bf16 operand of 2^31 bytes
+    or more is served by the plain kernels, which need no partial-sum workspace."""
+    bf16 = torch.bfloat16
+    below = rmm.rmm_workspace_bytes((1 << 20) - 128, 1016, 8, 70, bf16, 0, binding.OP_FORWARD)     # 2.13e9 bytes < 2^31
+    above = rmm.rmm_workspace_bytes((1 << 20) + 128, 1024, 8, 70, bf16, 0, binding.OP_FORWARD)     # 2^31 + ...
+    assert below > 0 and above == 0
