@@ -93,3 +93,11 @@ def stack_pool_inputs(shape, pool):
     d_out = STACK["d_ff"] if shape == "ffn_up" else STACK["d"]
     s = STACK["pool_seed_base"] + 10 * idx + 3 * pool
     return layer_inputs(STACK["n"], d_in, d_out, STACK["dtype"], (s, s + 1, s + 2))
+
+
+def pattern_rows(row0, rows, cols, mult, mod):
+    """Deterministic bf16-exact test matrix block (no random draw, so a multi-GiB operand can be
+    made in pieces on either side): entry (i, j) = ((mult * i + 7 * j) % mod - mod // 2) / 8."""
+    i = np.arange(row0, row0 + rows, dtype=np.int64)[:, None]
+    j = np.arange(cols, dtype=np.int64)[None, :]
+    return ((mult * i + 7 * j) % mod - mod // 2).astype(np.float64) / 8.0
