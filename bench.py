@@ -339,12 +339,14 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg["dtype"], "data": "synthetic",
         "config": {"workload": "%s: N=%d tokens, d_in=%d, d_out=%d, k=%d (%s sketch), %s, X,dY~N(0,1), "
-                               "W~N(0,0.02^2), %d rotating buffer sets"
-                               % (args.workload, n, d_in, d_out, k, args.kind, cfg["dtype"], len(sets)),
+                               "W~N(0,%s), %d rotating buffer sets"
+                               % (args.workload, n, d_in, d_out, k, args.kind, cfg["dtype"],
+                                  "0.02^2" if cfg["dtype"] == "bf16" else "1/d_in", len(sets)),
                    "flops_per_step": total_flops,
                    "saved_activation_bytes": saved, "plain_layer_saved_bytes": n * d_in * esize,
                    "saved_fraction": saved / (n * d_in * esize)},
-        "roofline": {"bound": "mfma", "kernel": KERNEL_NAME[dominant], "stage": dominant, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+        "roofline": {"bound": "mfma" if cfg["dtype"] == "bf16" else "alu",
+                     "kernel": KERNEL_NAME[dominant] if cfg["dtype"] == "bf16" else "gemm_plain_kernel (%s)" % dominant, "stage": dominant, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": read_traffic(args.workload, dominant),
                      "avg_launch_ms": dom_ms, "empty_event_pair_ms": empty_pair_ms,
                      "flops_per_launch": fl[dominant],
