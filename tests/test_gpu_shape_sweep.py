@@ -11,6 +11,7 @@ import torch
 import paper_2201_13195_amd as rmm
 from paper_2201_13195_amd import synth
 from oracle import rmm as o_rmm
+from parity import assert_close
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -56,3 +57,5 @@ def test_parity_on_switch_points_and_random_shapes(shape):
     print(shape, kind, {k_: "%.2e" % v for k_, v in errs.items()}, flush=True)
     for name, e in errs.items():
         assert e <= 1e-2, (shape, name, e)
+    for name, got, want in (("Y", Y, oY), ("X_proj", Xp, oXp), ("dX", dX, odX), ("dW", dW, odW)):
+        assert_close(got, want, name, "bf16", str(shape))

@@ -10,6 +10,7 @@ import torch
 import paper_2201_13195_amd as rmm
 from paper_2201_13195_amd import synth
 from oracle import rmm as o_rmm
+from parity import assert_close
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -96,6 +97,9 @@ def test_config5_stack():
         print("layer %3d %-8s" % (L["layer"], L["shape"]), {k_: "%.2e" % v for k_, v in errs.items()}, flush=True)
         for name, e in errs.items():
             assert e <= 1e-2, (L["layer"], name, e)
+        for name, g_, w_ in (("Y", got["Y"], oY), ("X_proj", xproj[L["layer"]], oXp), ("dX", got["dX"], odX),
+                             ("dW", got["dW"], odW)):
+            assert_close(g_, w_, name, "bf16", "stack layer %d" % L["layer"])
 
     # layers that share inputs but not the sketch state must differ; a second run must not
     assert not torch.equal(xproj[0], xproj[1])

@@ -82,3 +82,23 @@ def test_variance_stats_are_reproducible_and_check_workspace():
     with pytest.raises(rmm.RmmError) as e:
         rmm.rmm_variance_stats(X.to(DEV), dY.to(DEV), 100, rmm.RADEMACHER, ws=torch.empty(16, dtype=torch.uint8, device=DEV))
     assert e.value.status == -3
+
+
+def test_hand_cases_with_nonzero_cross_term(golden_dir):
+    """Lemma 2.1 and alpha of Theorem 2.3 on the hand-evaluated integer inputs of
+    tests/golden/variance_hand_cases.txt (X^T Y != 0), against the literals."""
+    n_cases = 0
+    with open(os.path.join(golden_dir, "variance_hand_cases.txt")) as f:
+        for line in f:
+            if not line.strip() or line.startswith("#"):
+                continue
+            t = [float(v) for v in line.split()]
+            B, N, M = int(t[0]), int(t[1]), int(t[2])
+            X = torch.tensor(t[3:3 + B * N], dtype=torch.float32).reshape(B, N)
+            Y = torch.tensor(t[3 + B * N:3 + B * N + B * M], dtype=torch.float32).reshape(B, M)
+            for dtype in (torch.float32, torch.bfloat16):       # small integers are exact in both
+                got = rmm.rmm_variance_stats(X.to(DEV).to(dtype), Y.to(DEV).to(dtype), 3, rmm.GAUSSIAN).cpu().numpy()
+                assert abs(got[4] - t[-2]) <= 1e-6 * max(1.0, abs(t[-2])), (line, got[4])
+                assert abs(got[6] - t[-1]) <= 1e-6, (line, got[6])
+            n_cases += 1
+    assert n_cases >= 4

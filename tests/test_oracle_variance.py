@@ -1,7 +1,8 @@
 """Pins for oracle.variance: the paper's B = 2 worked example (Section 2.3),
 Monte-Carlo variance of the estimate on correlated inputs (decides the sign in
 Lemma 2.2 and the Rademacher correction), the 1/k decay, a chi-square special
-case, and Theorem 2.3's bound."""
+case, Theorem 2.3's bound, and pins of Lemma 2.1 and of alpha that do not vanish (hand
+cases with X^T Y != 0, the definition the lemma's proof starts from, a row-sampling Monte-Carlo)."""
 import math
 import os
 
@@ -99,3 +100,81 @@ def test_theorem_bound_with_printed_lemma():
         assert 0.0 <= a <= 1.0
         lhs = k / (12 - 1) * variance.d2_rmm_printed(X, Y, k) / variance.d2_sgd(X, Y)
         assert lhs <= (a + 1) / a
+
+
+def _hand_cases(golden_dir):
+    cases = []
+    with open(os.path.join(golden_dir, "variance_hand_cases.txt")) as f:
+        for line in f:
+            if not line.strip() or line.startswith("#"):
+                continue
+            t = [float(v) for v in line.split()]
+            B, N, M = int(t[0]), int(t[1]), int(t[2])
+            X = np.array(t[3:3 + B * N]).reshape(B, N)
+            Y = np.array(t[3 + B * N:3 + B * N + B * M]).reshape(B, M)
+            cases.append((X, Y, t[-2], t[-1]))
+    assert len(cases) >= 4
+    return cases
+
+
+def test_hand_cases_with_nonzero_cross_term(golden_dir):
+    """Lemma 2.1 and Theorem 2.3's alpha on integer inputs worked out by hand, where the
+    |X^T Y|^2 term does not vanish (in the paper's own example it does)."""
+    for X, Y, want_sgd, want_alpha in _hand_cases(golden_dir):
+        assert np.any(X.T @ Y != 0.0)
+        assert math.isclose(variance.d2_sgd(X, Y), want_sgd, rel_tol=1e-13, abs_tol=1e-13)
+        assert math.isclose(variance.alpha(X, Y), want_alpha, rel_tol=1e-13)
+
+
+def test_d2_sgd_is_the_sample_variance_of_the_mean():
+    """The definition Lemma 2.1's proof starts from: Z_k = B x_k y_k^T has mean X^T Y, and
+    D2_SGD = 1/(B(B-1)) sum_k |Z_k - X^T Y|_F^2 (unbiased sample variance of Z, over B)."""
+    g = np.random.default_rng(21)
+    for B, N, M in ((2, 3, 2), (5, 4, 3), (9, 2, 6)):
+        X, Y = g.standard_normal((B, N)), 0.5 * g.standard_normal((B, M)) + 0.7
+        zbar = X.T @ Y
+        tot = 0.0
+        for kk in range(B):
+            Z = B * np.outer(X[kk], Y[kk])
+            tot += float(np.sum((Z - zbar) ** 2))
+        assert math.isclose(variance.d2_sgd(X, Y), tot / (B * (B - 1)), rel_tol=1e-12)
+
+
+def test_d2_sgd_against_row_sampling_monte_carlo():
+    """Lemma 2.1 estimates the noise of a gradient formed from randomly selected samples.  Draw B
+    rows with replacement from the B given ones: the mean of Z = B x y^T over the draw has
+    expectation X^T Y and mean squared deviation (population variance of Z) / B, which is
+    (B-1)/B * D2_SGD.  Inputs are correlated so that the cross term is a large part of the value."""
+    g = np.random.default_rng(22)
+    B = 6
+    X = g.standard_normal((B, 3)) + 1.0
+    Y = 0.6 * X[:, :2] + 0.2 * g.standard_normal((B, 2))
+    rows = float(np.sum(np.sum(X * X, axis=1) * np.sum(Y * Y, axis=1)))
+    assert np.sum((X.T @ Y) ** 2) > 0.25 * B * rows         # the cross term matters here
+    M = 200000
+    idx = g.integers(0, B, size=(M, B))
+    Zk = B * np.einsum("kn,km->knm", X, Y)                   # per-sample matrices
+    means = Zk[idx].mean(axis=1)                             # (M, N, M')
+    err2 = np.sum((means - (X.T @ Y)[None]) ** 2, axis=(1, 2))
+    mc, se = err2.mean(), err2.std(ddof=1) / math.sqrt(M)
+    want = (B - 1) / B * variance.d2_sgd(X, Y)
+    assert abs(mc - want) < 5 * se and abs(mc - want) < 0.02 * want
+    # dropping the cross term, flipping its sign or halving it is far outside the Monte-Carlo error
+    cross = float(np.sum((X.T @ Y) ** 2)) / (B - 1.0) * (B - 1) / B
+    assert 0.5 * cross > 20 * se
+
+
+def test_alpha_special_cases():
+    """Theorem 2.3's alpha = |X^T Y|^2 / (|X|^2 |Y|^2): 1 for X = Y = one column, 0 for orthogonal
+    columns, cos^2 of the angle for two single columns, invariant under scaling of X and of Y."""
+    a = np.array([[1.0], [2.0], [-0.5]])
+    assert math.isclose(variance.alpha(a, a), 1.0, rel_tol=1e-14)
+    assert variance.alpha(np.array([[1.0], [1.0]]), np.array([[1.0], [-1.0]])) == 0.0
+    u, v = np.array([[1.0], [0.0]]), np.array([[1.0], [1.0]])
+    assert math.isclose(variance.alpha(u, v), 0.5, rel_tol=1e-14)
+    g = np.random.default_rng(23)
+    X, Y = g.standard_normal((7, 3)), g.standard_normal((7, 4))
+    assert math.isclose(variance.alpha(3.0 * X, -0.25 * Y), variance.alpha(X, Y), rel_tol=1e-12)
+    # entry-wise statement: sum over pairs of columns of squared inner products, over the product of norms
+    tot = sum(float(X[:, p] @ Y[:, q]) ** 2 for p in range(3) for q in range(4))
+    assert math.isclose(variance.alpha(X, Y), tot / (float(np.sum(X * X)) * float(np.sum(Y * Y))), rel_tol=1e-12)
