@@ -22,7 +22,8 @@
  *   - Return value: RMM_OK or a negative rmm_status_t.  Nothing is printed, no
  *     exception crosses the boundary, the process is never aborted.  On an
  *     error return no kernel has been launched.
- *   - The library holds no mutable global state; calls are re-entrant.
+ *   - The library holds no mutable global state and calls are re-entrant; the one exception is
+ *     rmm_sketch_static, whose scratch array is shared by all calls on a GPU (see there).
  *   - dtype RMM_DTYPE_BF16: inputs, Y, dX, X_proj, dW are bfloat16 (round to
  *     nearest even from fp32 accumulators); bias / dbias are bfloat16 too.
  *     dtype RMM_DTYPE_F32: everything is fp32.
@@ -57,7 +58,8 @@ typedef enum {
     RMM_ERR_INVALID_ARG = -1, /* NULL required pointer, non-positive size, unknown enum, misaligned pointer */
     RMM_ERR_UNSUPPORTED = -2, /* sizes beyond the documented limits */
     RMM_ERR_WORKSPACE = -3,   /* ws is NULL or ws_bytes is below rmm_workspace_bytes() */
-    RMM_ERR_LAUNCH = -4       /* the HIP runtime refused a launch */
+    RMM_ERR_LAUNCH = -4,      /* the HIP runtime refused a launch */
+    RMM_ERR_SCRATCH_LIMIT = -5 /* rmm_sketch_static only: the shape needs more than RMM_STATIC_SCRATCH_BYTES */
 } rmm_status_t;
 
 typedef enum { RMM_DTYPE_F32 = 0, RMM_DTYPE_BF16 = 1 } rmm_dtype_t;
@@ -95,6 +97,21 @@ int rmm_version(void);
  * A: device, read only.  A_proj: device, written.  Output dtype = dtype. */
 int rmm_sketch(int64_t n, int64_t d, int64_t k, int dtype, int kind, rmm_rng_state_t state,
                const void *A, void *A_proj, void *ws, size_t ws_bytes, void *stream);
+
+/* rmm_sketch for callers that cannot allocate or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results (bit for bit) and
+ * errors as rmm_sketch, but the scratch the kernels need (fp32 partial sums of the token slices) is
+ * a fixed array of RMM_STATIC_SCRATCH_BYTES inside the library's device code, one copy per GPU,
+ * held until the process ends.  A shape whose rmm_workspace_bytes(desc, RMM_OP_SKETCH) exceeds that
+ * size is refused with RMM_ERR_SCRATCH_LIMIT before anything is launched.  The call allocates and
+ * frees nothing (its first use on a device looks the array's address up once).  All calls on one
+ * GPU share the array: two calls that may run at the same time on one GPU (different streams, or
+ * different host threads) race and must be serialised by the caller; calls on one stream are
+ * ordered.  The array keeps the last call's contents; every call overwrites what it later reads,
+ * nothing needs to start at zero. */
+#define RMM_STATIC_SCRATCH_BYTES (32u << 20)
+int rmm_sketch_static(int64_t n, int64_t d, int64_t k, int dtype, int kind, rmm_rng_state_t state,
+                      const void *A, void *A_proj, void *stream);
 
 /* Algorithm 1, Forward: Y[n x d_out] = X[n x d_in] W[d_out x d_in]^T (+ bias[d_out] on
  * every row if bias != NULL; Eq. 1), X_proj[k x d_in] = S^T X.  After the call the

@@ -55,6 +55,8 @@ def load_library():
     L.rmm_sketch.argtypes = [i64, i64, i64, ci, ci, _State, vp, vp, vp, sz, vp]
     L.rmm_sketch_profiled.restype = ci
     L.rmm_sketch_profiled.argtypes = L.rmm_sketch.argtypes + [vp, vp]
+    L.rmm_sketch_static.restype = ci
+    L.rmm_sketch_static.argtypes = [i64, i64, i64, ci, ci, _State, vp, vp, vp]
     L.rmm_forward.restype = ci
     L.rmm_forward.argtypes = [ctypes.POINTER(_Desc), _State, vp, vp, vp, vp, vp, vp, sz, vp]
     L.rmm_backward.restype = ci
@@ -134,6 +136,20 @@ def rmm_sketch(A, k, kind, seed, offset, out=None, ws=None, events=None):
                                             _ptr(out, "out", A.dtype, (k, d)), wsp, wsb, _stream(A), evb, eve)
     if rc != 0:
         raise RmmError(rc, "rmm_sketch")
+    return out
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def rmm_sketch_static(A, k, kind, seed, offset, out):
+    """rmm_sketch on the library's own static scratch: no workspace, no allocation (the caller
+    passes `out`).  Raises RmmError(-5) when the shape needs more than STATIC_SCRATCH_BYTES."""
+    n, d = A.shape
+    rc = load_library().rmm_sketch_static(n, d, k, _DTYPES[A.dtype], kind, _State(seed, offset), _ptr(A, "A"),
+                                          _ptr(out, "out", A.dtype, (k, d)), _stream(A))
+    if rc != 0:
+        raise RmmError(rc, "rmm_sketch_static")
     return out
 
 

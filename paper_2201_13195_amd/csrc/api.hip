@@ -4,6 +4,8 @@
 
 #include <math.h>
 
+#include <mutex>
+
 #include "common.hpp"
 
 using namespace rmm;
@@ -58,6 +60,30 @@ size_t ws_variance(const rmm_layer_desc_t *d) {
 }
 
 int from_hip(hipError_t e) { return e == hipSuccess ? RMM_OK : RMM_ERR_LAUNCH; }
+
+// Scratch of rmm_sketch_static: device memory that is part of the library's code object, so that
+// entry point needs no workspace argument and no allocation.  In host code the array's name is
+// only a handle for hipGetSymbolAddress; kernels and copies get the per-device address kept in
+// g_static_scratch (every GPU holds its own copy of the array at its own address).
+constexpr size_t kStaticScratchBytes = (size_t)RMM_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void *g_static_scratch[kMaxDevices];
+std::mutex g_static_scratch_mutex;
+
+// Address of the current device's copy of `scratch` (looked up once per device).
+int static_scratch_ptr(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return RMM_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+    if (g_static_scratch[dev] == nullptr) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return RMM_ERR_LAUNCH;
+        g_static_scratch[dev] = p;
+    }
+    *out = g_static_scratch[dev];
+    return RMM_OK;
+}
 
 // Optional pair of caller-owned events bracketing one stage of a pass.
 struct StageEvents {
@@ -163,6 +189,7 @@ const char *rmm_status_string(int status) {
         case RMM_ERR_UNSUPPORTED: return "size beyond the supported limits";
         case RMM_ERR_WORKSPACE: return "workspace missing or too small";
         case RMM_ERR_LAUNCH: return "HIP launch failed";
+        case RMM_ERR_SCRATCH_LIMIT: return "shape needs more scratch than the library's static buffer holds";
         default: return "unknown status";
     }
 }
@@ -204,6 +231,25 @@ int rmm_sketch_profiled(int64_t n, int64_t d, int64_t k, int dtype, int kind, rm
 int rmm_sketch(int64_t n, int64_t d, int64_t k, int dtype, int kind, rmm_rng_state_t state, const void *A,
                void *A_proj, void *ws, size_t ws_bytes, void *stream) {
     return rmm_sketch_profiled(n, d, k, dtype, kind, state, A, A_proj, ws, ws_bytes, stream, nullptr, nullptr);
+}
+
+int rmm_sketch_static(int64_t n, int64_t d, int64_t k, int dtype, int kind, rmm_rng_state_t state, const void *A,
+                      void *A_proj, void *stream) {
+    rmm_layer_desc_t desc = {n, d, d, k, dtype, kind};
+    if (!desc_ok(&desc) || A == nullptr || A_proj == nullptr) return RMM_ERR_INVALID_ARG;
+    if (!aligned16(A) || !aligned16(A_proj)) return RMM_ERR_INVALID_ARG;
+    if (!grid_ok(k)) return RMM_ERR_UNSUPPORTED;
+    const size_t need = ws_sketch(&desc);
+    if (need > kStaticScratchBytes) return RMM_ERR_SCRATCH_LIMIT;
+    void *ws = nullptr;
+    if (need > 0) {  // the only HIP calls besides the launches: no allocation, no copy, no wait
+        const int rc = static_scratch_ptr(&ws);
+        if (rc != RMM_OK) return rc;
+    }
+    const SketchState st = make_state(state.seed, state.offset);
+    hipStream_t s = (hipStream_t)stream;
+    return dtype == RMM_DTYPE_BF16 ? sketch_impl<bf16_t>(n, d, k, kind, st, A, A_proj, use_mfma(&desc), ws, s)
+                                   : sketch_impl<float>(n, d, k, kind, st, A, A_proj, false, ws, s);
 }
 
 int rmm_forward_profiled(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *X, const void *W,

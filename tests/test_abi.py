@@ -37,8 +37,8 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_status_strings(lib):
-    seen = {rmm.rmm_status_string(s) for s in (0, -1, -2, -3, -4)}
-    assert len(seen) == 5
+    seen = {rmm.rmm_status_string(s) for s in (0, -1, -2, -3, -4, -5)}
+    assert len(seen) == 6
     assert rmm.rmm_status_string(-99) == "unknown status"
     assert rmm.rmm_version() >= 100
 
@@ -136,6 +136,11 @@ def test_new_entry_points_validate_before_launching(lib):
     assert lib.rmm_backward_accumulate(ctypes.byref(good), st, fake, fake, fake, fake, None, None, None, 0, None) == -1
     assert lib.rmm_backward_accumulate(ctypes.byref(good), st, fake, fake, fake, fake, fake, None, None, 0, None) == -3
     assert lib.rmm_sketch_profiled(0, 4, 4, 0, 0, st, fake, fake, None, 0, None, None, None) == -1
+    # the entry point on the library's static scratch: argument errors, then its size limit
+    assert lib.rmm_sketch_static(0, 4, 4, 0, 0, st, fake, fake, None) == -1
+    assert lib.rmm_sketch_static(8, 4, 4, 0, 0, st, fake, ctypes.c_void_p(0x1004), None) == -1
+    assert rmm.rmm_workspace_bytes(16384, 4096, 4096, 1638, torch.bfloat16, 0, binding.OP_SKETCH) > rmm.STATIC_SCRATCH_BYTES
+    assert lib.rmm_sketch_static(16384, 4096, 1638, 1, 0, st, fake, fake, None) == -5
 
 
 def test_operands_of_two_gib_or_more_leave_the_mfma_path(lib):

@@ -1,0 +1,49 @@
+"""GPU: rmm_sketch_static (the entry point for callers that cannot allocate: its scratch is a
+fixed array inside the library) against rmm_sketch, through the C ABI, on two calls in a row, the
+second with a smaller input, and its size limit."""
+import ctypes
+
+import pytest
+import torch
+
+import paper_2201_13195_amd as rmm
+from paper_2201_13195_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _pair(n, d, k, kind, seed, offset, data_seed):
+    A = synth.to_torch(synth.normal((n, d), data_seed), "bf16").to(DEV)
+    need = rmm.rmm_workspace_bytes(n, d, d, k, torch.bfloat16, kind, binding.OP_SKETCH)
+    assert 0 < need <= rmm.STATIC_SCRATCH_BYTES, (n, d, k, need)   # the case must use the scratch at all
+    want = rmm.rmm_sketch(A, k, kind, seed, offset)
+    out = torch.full((k, d), float("nan"), dtype=torch.bfloat16, device=DEV)
+    got = rmm.rmm_sketch_static(A, k, kind, seed, offset, out)
+    torch.cuda.synchronize()
+    return got, want
+
+
+@pytest.mark.parametrize("kind", [rmm.GAUSSIAN, rmm.RADEMACHER])
+def test_static_scratch_matches_workspace_entry_point_twice_in_a_row(kind):
+    # same kernels, same summation order: the bits must agree, not just the values
+    got, want = _pair(4100, 1032, 410, kind, 0x5EED00A1, 5, 61)      # several token slices, ragged edges
+    assert torch.equal(got, want)
+    got, want = _pair(1500, 520, 77, kind, 0x5EED00A1, 6, 62)        # smaller: the scratch holds stale partials
+    assert torch.equal(got, want)
+    got, want = _pair(3000, 264, 33, kind, 0x5EED00A1, 7, 63)        # the streaming kernel (k <= 64)
+    assert torch.equal(got, want)
+
+
+def test_static_scratch_limit_is_an_error_code():
+    """A shape that needs more scratch than the array holds is refused before any launch."""
+    lib = rmm.load_library()
+    n, d, k = 16384, 4096, 1638
+    assert rmm.rmm_workspace_bytes(n, d, d, k, torch.bfloat16, 0, binding.OP_SKETCH) > rmm.STATIC_SCRATCH_BYTES
+    fake = ctypes.c_void_p(0x1000)      # never dereferenced: the size check comes first
+    assert lib.rmm_sketch_static(n, d, k, 1, 0, binding._State(1, 2), fake, fake, None) == -5
+    assert "scratch" in rmm.rmm_status_string(-5)
+    # fp32 shapes need no scratch at all and are served
+    A = synth.to_torch(synth.normal((300, 40), 64), "f32").to(DEV)
+    out = torch.empty((9, 40), dtype=torch.float32, device=DEV)
+    assert torch.equal(rmm.rmm_sketch_static(A, 9, 0, 3, 4, out), rmm.rmm_sketch(A, 9, 0, 3, 4))
