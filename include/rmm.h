@@ -164,7 +164,14 @@ typedef enum {
      * the token-slice partial results (identical to the stage when the library
      * uses a single slice). */
     RMM_STAGE_FWD_XPROJ_PRODUCT = 6,
-    RMM_STAGE_BWD_G_PRODUCT = 7
+    RMM_STAGE_BWD_G_PRODUCT = 7,
+    /* Where the library issues the two independent products of a pass (Y with X_proj, dX with G)
+     * as ONE kernel launch, so that each takes the compute units the other leaves idle: that
+     * kernel alone.  Asking for one of the stages 0-3, 6 or 7 makes the call launch the two
+     * products one after the other instead (same results, bit for bit), so that each can be timed;
+     * a call that launches them separately anyway records nothing for these two. */
+    RMM_STAGE_FWD_PAIR = 8,
+    RMM_STAGE_BWD_PAIR = 9
 } rmm_stage_t;
 
 /* Measurement hooks: identical to rmm_forward / rmm_backward, and in addition

@@ -174,6 +174,7 @@ def rmm_variance_stats(X, dY, k, kind, out=None, ws=None):
 
 STAGE_FWD_Y, STAGE_FWD_XPROJ, STAGE_BWD_DX, STAGE_BWD_G, STAGE_BWD_DW, STAGE_BWD_DBIAS = range(6)
 STAGE_FWD_XPROJ_PRODUCT, STAGE_BWD_G_PRODUCT = 6, 7
+STAGE_FWD_PAIR, STAGE_BWD_PAIR = 8, 9     # the one-launch kernel for Y with X_proj / dX with G, where the library has one
 
 
 def _event_args(profile):

@@ -61,6 +61,12 @@ size_t ws_variance(const rmm_layer_desc_t *d) {
 
 int from_hip(hipError_t e) { return e == hipSuccess ? RMM_OK : RMM_ERR_LAUNCH; }
 
+// Stages that exist only when the two independent products of a pass are launched one by one.
+bool separate_stage(int stage) {
+    return stage == RMM_STAGE_FWD_Y || stage == RMM_STAGE_FWD_XPROJ || stage == RMM_STAGE_FWD_XPROJ_PRODUCT ||
+           stage == RMM_STAGE_BWD_DX || stage == RMM_STAGE_BWD_G || stage == RMM_STAGE_BWD_G_PRODUCT;
+}
+
 // Scratch of rmm_sketch_static: device memory that is part of the library's code object, so that
 // entry point needs no workspace argument and no allocation.  In host code the array's name is
 // only a handle for hipGetSymbolAddress; kernels and copies get the per-device address kept in
@@ -125,6 +131,12 @@ template <typename T>
 int forward_impl(const rmm_layer_desc_t *d, SketchState st, const void *X, const void *W, const void *bias, void *Y,
                  void *X_proj, void *ws, hipStream_t stream, const StageEvents &ev) {
     const bool mfma = use_mfma(d);
+    if (mfma && !separate_stage(ev.stage) && forward_pair_available(d->n, d->d_in, d->d_out, d->k)) {
+        const bool timed = ev.stage == RMM_STAGE_FWD_PAIR;
+        return from_hip(launch_forward_pair_bf16((const bf16_t *)X, (const bf16_t *)W, (const bf16_t *)bias, (bf16_t *)Y,
+                                                 (bf16_t *)X_proj, d->n, d->d_in, d->d_out, d->k, d->kind, st, ws, stream,
+                                                 timed ? ev.begin : nullptr, timed ? ev.end : nullptr));
+    }
     {   // Y = X W^T (+ bias): A = X (n x d_in), B(kk, c) = W[c][kk].
         StageScope scope(ev, RMM_STAGE_FWD_Y, stream);
         hipError_t e =
@@ -145,7 +157,17 @@ int backward_impl(const rmm_layer_desc_t *d, SketchState st, const void *dY, con
                   bool accumulate) {
     hipError_t e;
     const bool mfma = use_mfma(d);
-    if (dX != nullptr) {  // dX = dY W: B(kk, c) = W[kk][c]
+    T *G = (T *)ws;  // G = S^T dY, k x d_out
+    const bool paired = mfma && dX != nullptr && !separate_stage(ev.stage) &&
+                        backward_pair_available(d->n, d->d_in, d->d_out, d->k);
+    if (paired) {
+        const bool timed = ev.stage == RMM_STAGE_BWD_PAIR;
+        e = launch_backward_pair_bf16((const bf16_t *)dY, (const bf16_t *)W, (bf16_t *)dX, (bf16_t *)G, d->n, d->d_in,
+                                      d->d_out, d->k, d->kind, st, (char *)ws + g_bytes(d), stream,
+                                      timed ? ev.begin : nullptr, timed ? ev.end : nullptr);
+        if (e != hipSuccess) return RMM_ERR_LAUNCH;
+    }
+    if (!paired && dX != nullptr) {  // dX = dY W: B(kk, c) = W[kk][c]
         StageScope scope(ev, RMM_STAGE_BWD_DX, stream);
         e = mfma ? launch_linear_nn_bf16((const bf16_t *)dY, (const bf16_t *)W, (bf16_t *)dX, d->n, d->d_in, d->d_out,
                                          stream)
@@ -153,8 +175,7 @@ int backward_impl(const rmm_layer_desc_t *d, SketchState st, const void *dY, con
                                            (const T *)nullptr, d->n, d->d_in, d->d_out, 1.0f, stream);
         if (e != hipSuccess) return RMM_ERR_LAUNCH;
     }
-    T *G = (T *)ws;  // G = S^T dY, k x d_out
-    {
+    if (!paired) {
         StageScope scope(ev, RMM_STAGE_BWD_G, stream);
         int rc = sketch_impl<T>(d->n, d->d_out, d->k, d->kind, st, dY, G, mfma, (char *)ws + g_bytes(d), stream, ev,
                                 RMM_STAGE_BWD_G_PRODUCT);

@@ -68,6 +68,20 @@ hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d
                               void *ws, hipStream_t stream, hipEvent_t ev_begin = nullptr,
                               hipEvent_t ev_end = nullptr);
 
+// One launch for the two products of a pass that do not depend on each other: Y = X W^T (+ bias)
+// with the sketch product of X (forward), dX = dY W with the sketch product of dY (backward; G is
+// k x d_out), followed by the sum over the sketch's token slices.  Results are bit-identical to
+// the separate launches above (same kernels, same slices).  Only where *_pair_available() says so;
+// the optional event pair brackets the paired kernel alone.
+bool forward_pair_available(int64_t n, int64_t d_in, int64_t d_out, int64_t k);
+hipError_t launch_forward_pair_bf16(const bf16_t *X, const bf16_t *W, const bf16_t *bias, bf16_t *Y, bf16_t *X_proj,
+                                    int64_t n, int64_t d_in, int64_t d_out, int64_t k, int kind, SketchState st, void *ws,
+                                    hipStream_t stream, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
+bool backward_pair_available(int64_t n, int64_t d_in, int64_t d_out, int64_t k);
+hipError_t launch_backward_pair_bf16(const bf16_t *dY, const bf16_t *W, bf16_t *dX, bf16_t *G, int64_t n, int64_t d_in,
+                                     int64_t d_out, int64_t k, int kind, SketchState st, void *ws, hipStream_t stream,
+                                     hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
+
 // Variance monitors (variance.hip, and the squared-norm epilogue of the MFMA kernel).
 //   part[3*b..] = per-block (sum |x_k|^2, sum |y_k|^2, sum |x_k|^2 |y_k|^2); row_norm_blocks(n) blocks.
 int row_norm_blocks(int64_t n);

@@ -1,985 +1,198 @@
-// bf16 MFMA kernels of the RMM layer (gfx950).
-//
-// One tiled-GEMM kernel template covers the five products of Algorithm 1:
-//
-//   Y      = X W^T          A = X  (K-contiguous rows)      B = W      (K-contiguous rows)
-//   dX     = dY W           A = dY (K-contiguous rows)      B = W      (N-contiguous rows)
-//   X_proj = S^T X          A = P^T generated in registers  B = X      (N-contiguous rows)
-//   G      = S^T dY         A = P^T generated in registers  B = dY     (N-contiguous rows)
-//   dW     = G^T X_proj     A = G  (M-contiguous rows)      B = X_proj (N-contiguous rows)
-//
-// with C[M x N] = alpha * sum_kk A(m, kk) B(kk, n).  The contraction runs on
-// v_mfma_f32_32x32x16_bf16 with fp32 accumulators.  Memory operands are staged
-// through LDS in 16-byte chunks, double buffered.  An operand whose contraction
-// index is its row index ("N-contiguous" / "M-contiguous") is read back from LDS
-// with the transposing load ds_read_b64_tr_b16, which hands every lane four
-// consecutive contraction elements of one column.  The sketch operand is never
-// in memory: every lane makes the eight entries its MFMA operand register holds
-// from one Philox-4x32-10 call (Gaussian: the call's 8 Box-Muller values are
-// exactly 8 consecutive tokens of one sketch column; Rademacher: one byte of the
-// call's 128 sign bits).  The 1/sqrt(k) of S = P/sqrt(k) is applied to the fp32
-// accumulator, so P is exact in bf16 for Rademacher and rounded once for Gaussian.
-#include "common.hpp"
-
-#include <type_traits>
+// bf16 MFMA path of the RMM layer: which kernel of mfma_kernels.hpp serves which product at
+// which shape, and the launches.
+#include "mfma_pair.hpp"
 
 namespace rmm {
 
 namespace {
 
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-typedef short s16x4_t __attribute__((ext_vector_type(4)));
-typedef short s16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
-typedef float f32x2_t __attribute__((ext_vector_type(2)));
-typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
-
-// A operand: loaded K-contiguous / loaded row-indexed / sketch generated in registers (2, 3) /
-// sketch generated by the whole work-group into the K-contiguous LDS tile (4, 5).
-enum { A_KCONTIG = 0, A_MCONTIG = 1, A_GAUSS = 2, A_RADEM = 3, A_GAUSS_LDS = 4, A_RADEM_LDS = 5 };
-enum { B_KCONTIG = 0, B_NCONTIG = 1 };
-// Output: rounded to bf16 / fp32 partial result of a contraction slice / no matrix at all, only
-// the sum of squares of the tile (one double per work-group, C = double[work-groups]).
-enum { OUT_BF16 = 0, OUT_F32_PARTIAL = 1, OUT_SUMSQ = 2 };
-#ifndef RMM_TUNE_STORE_KS
-#define RMM_TUNE_STORE_KS 1
-#endif
-
-// K-contiguous LDS tiles are not padded: row r keeps its 16-byte chunk c at chunk position
-// c ^ ((r / (16 / U)) % U), U = chunks per row.  Then the 16 lanes that the LDS serves together hit
-// 16 different 16-byte bank groups both when a tile is written (consecutive lanes = consecutive
-// chunks of U-chunk rows) and when fragments are read (consecutive lanes = consecutive rows, same
-// chunk); a padded layout can only make one of the two conflict-free.
-template <int BK>
-__device__ __forceinline__ int kchunk_pos(int row, int chunk) {
-    constexpr int U = BK / 8, G = 16 / U;
-    static_assert(U == 4 || U == 8 || U == 16, "BK of 32, 64 or 128");
-    return chunk ^ ((row / G) % U);
-}
-constexpr int TPAD = 32;  // elements of padding per row of a transposed-read LDS tile (row stride = 64 mod 256 B)
-
-struct GemmArgs {
-    const bf16_t *A;
-    int64_t lda;
-    const bf16_t *B;
-    int64_t ldb;
-    void *C;
-    int64_t ldc;
-    const bf16_t *bias;
-    int64_t M, N, K;
-    int64_t a_bytes, b_bytes;  // byte sizes of the A and B operands in memory (each below 2^31)
-    float alpha;
-    int accumulate;        // bf16 output only: add the value C holds (in fp32, before the one rounding)
-    SketchState st;
-    int64_t k_chunk;       // contraction elements per blockIdx.z slice (multiple of 128)
-    int64_t split_stride;  // fp32 elements between the partial results of two slices
-#ifdef RMM_DEBUG_TRACE
-    unsigned long long *trace;
-#endif
-};
-
-// Eight unscaled Gaussian entries P[8*c0 .. 8*c0+7][j] as a bf16 MFMA operand.
-__device__ __forceinline__ bf16x8_t gauss_operand(const SketchState &st, uint32_t c0, uint32_t j) {
-    const Words4 r = philox4x32_10(c0, j, st.off0, st.off1, st.key0, st.key1);
-    union {
-        bf16x8_t v;
-        bf16x2_t p[4];
-    } out;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const uint32_t w = r.w[q];
-        const float u1 = (float)(2u * (w >> 16) + 1u) * (1.0f / 131072.0f);
-        const float u2 = (float)(w & 0xFFFFu) * (1.0f / 65536.0f);                            // revolutions
-        const float rad = __builtin_amdgcn_sqrtf(-1.3862943611198906f * __builtin_amdgcn_logf(u1));  // -2 ln2 log2 u1
-        f32x2_t z = {rad * __builtin_amdgcn_cosf(u2), rad * __builtin_amdgcn_sinf(u2)};
-        out.p[q] = __builtin_convertvector(z, bf16x2_t);
-    }
-    return out.v;
+// Prefetch depth (register sets of tiles in flight).  The kernels run whole groups of `depth`
+// tiles, so a plain product takes the one of 4 and 3 that pads its contraction less; the
+// 256 x 256 kernel and the sketch kernels need their registers for wide wave tiles and use 3.
+int plain_depth(int64_t contraction, int bk) {
+    const int64_t kt = (contraction + bk - 1) / bk;
+    const int64_t pad4 = (kt + 3) / 4 * 4 - kt, pad3 = (kt + 2) / 3 * 3 - kt;
+    return pad4 <= pad3 ? 4 : 3;
 }
 
-// Eight Rademacher entries for tokens t0 .. t0+7 (t0 a multiple of 8) of column j,
-// given the four words of the call that covers tokens 128*(t0/128) .. +127.
-__device__ __forceinline__ bf16x8_t radem_operand(const Words4 &r, uint32_t t0) {
-    const uint32_t t = t0 & 127u;
-    const uint32_t word = (t >> 5) == 0 ? r.w[0] : (t >> 5) == 1 ? r.w[1] : (t >> 5) == 2 ? r.w[2] : r.w[3];
-    const uint32_t bits = (word >> (t & 31u)) & 0xFFu;
-    union {
-        bf16x8_t v;
-        uint32_t d[4];
-    } out;
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-        out.d[q] = 0x3F803F80u | (((bits >> (2 * q)) & 1u) << 15) | (((bits >> (2 * q + 1)) & 1u) << 31);
-    return out.v;
-}
-
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int WAVES_K, int AMODE, int BMODE, int OUT>
-struct Tile {
-    static constexpr int THREADS = 64 * WAVES_M * WAVES_N * WAVES_K;  // WAVES_K groups of waves split the contraction
-    static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // wave tile
-    static constexpr int TM = WTM / 32, TN = WTN / 32;            // 32x32 MFMA tiles per wave
-    static constexpr bool A_GEN_LDS = (AMODE == A_GAUSS_LDS || AMODE == A_RADEM_LDS);
-    static constexpr bool A_KLAYOUT = (AMODE == A_KCONTIG || A_GEN_LDS);  // LDS tile [row][contraction]
-    static constexpr bool A_IN_LDS = (A_KLAYOUT || AMODE == A_MCONTIG);
-    static constexpr int A_STRIDE = A_KLAYOUT ? BK : BM + TPAD;  // elements per LDS row
-    static constexpr int A_ROWS = A_KLAYOUT ? BM : BK;
-    static constexpr int B_STRIDE = BMODE == B_KCONTIG ? BK : BN + TPAD;
-    static constexpr int B_ROWS = BMODE == B_KCONTIG ? BN : BK;
-    static constexpr int A_ELEMS = A_IN_LDS ? A_ROWS * A_STRIDE : 0;
-    static constexpr int B_ELEMS = B_ROWS * B_STRIDE;
-    static constexpr int STAGE_ELEMS = A_ELEMS + B_ELEMS;
-    static constexpr int STAGES = 3;  // LDS stages: tile t is computed while tile t+2 is written
-    static constexpr int LDS_BYTES = STAGES * STAGE_ELEMS * 2;
-    // 16-byte chunks per thread and tile.  A generated A tile may have fewer chunks than the
-    // work-group has threads (then whole waves generate nothing).
-    static constexpr int A_CHUNKS = A_IN_LDS ? (BM * BK / 8 + THREADS - 1) / THREADS : 0;
-    static constexpr int B_CHUNKS = BN * BK / 8 / THREADS;
-    static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0 && BK % (16 * WAVES_K) == 0, "tile shape");
-    static_assert((A_GEN_LDS ? (BM * BK / 8) % 64 == 0 : (BM * BK / 8) % THREADS == 0) && (BN * BK / 8) % THREADS == 0,
-                  "chunks per thread");
-};
-
-// Operand fragment of the 32x32x16 MFMA from a K-contiguous LDS tile (rows of BK elements,
-// chunks placed by kchunk_pos): lane l holds row (l % 32), contraction elements 8*(l / 32) .. +7.
-template <int BK>
-__device__ __forceinline__ bf16x8_t frag_kcontig(const bf16_t *tile, int row0, int kk0, int lane) {
-    const int row = row0 + (lane & 31), chunk = (kk0 >> 3) + (lane >> 5);
-    return *reinterpret_cast<const bf16x8_t *>(tile + row * BK + kchunk_pos<BK>(row, chunk) * 8);
-}
-
-// Same fragment from a tile stored [contraction row][column]: two transposing
-// reads.  Within a block of 16 lanes, lane i points at row (i / 4), columns
-// 4*(i % 4) .. +3 of a 4 x 16 patch; the load returns to lane L the four rows of
-// column L.  Block b of the wave covers columns 16*(b % 2) .. +15 and
-// contraction rows 8*(b / 2) .. +7 (in two patches of four rows).
-__device__ __forceinline__ bf16x8_t frag_transposed(const bf16_t *tile, int stride, int col0, int kk0, int lane) {
-    const int blk = lane >> 4, i = lane & 15;
-    const bf16_t *p = tile + (kk0 + ((blk >> 1) << 3) + (i >> 2)) * stride + col0 + ((blk & 1) << 4) + ((i & 3) << 2);
-    typedef __attribute__((address_space(3))) s16x4_t *lds_ptr_t;
-    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p));
-    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 4 * stride));
-    union {
-        s16x8_t s;
-        bf16x8_t v;
-    } out;
-    out.s = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return out.v;
-}
-
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int WAVES_K, int AMODE, int BMODE, int OUT, int D>
-__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N * WAVES_K) gemm_mfma_kernel(GemmArgs g) {
-    typedef Tile<BM, BN, BK, WAVES_M, WAVES_N, WAVES_K, AMODE, BMODE, OUT> T;
-    __shared__ __attribute__((aligned(16))) bf16_t lds[T::STAGES * T::STAGE_ELEMS];
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // Wave w works on the (wm, wn) part of the tile and, of every 16-deep contraction step s,
-    // on those with s % WAVES_K == kg.
-    const int kg = wave / (WAVES_M * WAVES_N), wmn = wave % (WAVES_M * WAVES_N);
-    const int wm = wmn / WAVES_N, wn = wmn % WAVES_N;
-    // Tile order.  Work-groups are dealt round-robin to the 8 XCDs (each with its own L2), so first
-    // renumber them such that one XCD owns a contiguous run of positions; then walk the tile grid
-    // in bands of GROUP_M tile rows, column by column, so that the work-groups resident on one XCD
-    // at the same time form a compact block that shares A row blocks and B column blocks in L2.
-    const int64_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-    const int64_t tiles = (int64_t)gridDim.x;
-    int64_t tile = blockIdx.x;
-    {
-        const int64_t per = tiles / 8, rem = tiles % 8, x = tile % 8, r = tile / 8;
-        tile = x * per + (x < rem ? x : rem) + r;   // XCD x owns `per` (+1 for the first `rem`) consecutive positions
-    }
-    constexpr int64_t GROUP_M = 8;
-    const int64_t band = tile / (GROUP_M * tiles_n), in_band = tile % (GROUP_M * tiles_n);
-    const int64_t band_rows = min(GROUP_M, tiles_m - band * GROUP_M);
-    const int64_t m0 = (band * GROUP_M + in_band % band_rows) * BM, n0 = (in_band / band_rows) * BN;
-    const int64_t kk_begin = (int64_t)blockIdx.z * g.k_chunk;
-    const int64_t kk_end = min(g.K, kk_begin + g.k_chunk);
-    const int num_tiles = kk_end > kk_begin ? (int)((kk_end - kk_begin + BK - 1) / BK) : 0;
-
-    f32x16_t acc[T::TM][T::TN];
-#pragma unroll
-    for (int a = 0; a < T::TM; ++a)
-#pragma unroll
-        for (int b = 0; b < T::TN; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
-
-    // Global loads are buffer loads: an offset at or beyond the operand's byte size returns zeros
-    // without touching memory, so tile edges and the tail of the contraction need no branches (a
-    // chunk that must read as zero is simply given the offset 2^31).  Matrices are below 2^31 bytes.
-    const __amdgpu_buffer_rsrc_t rsrc_a =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(g.A), (short)0, (int)g.a_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrc_b =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(g.B), (short)0, (int)g.b_bytes, 0x00020000);
-    constexpr uint32_t OOB = 0x80000000u;
-
-    // Per 16-byte chunk of a tile: byte offset in the operand for the first tile of this slice,
-    // whether its row / column group exists at all, and its position along the contraction.
-    uint32_t a_off[T::A_CHUNKS > 0 ? T::A_CHUNKS : 1], b_off[T::B_CHUNKS];
-    bool a_ok[T::A_CHUNKS > 0 ? T::A_CHUNKS : 1], b_ok[T::B_CHUNKS];
-    int a_kk[T::A_CHUNKS > 0 ? T::A_CHUNKS : 1], b_kk[T::B_CHUNKS];
-    int a_lds[T::A_CHUNKS > 0 ? T::A_CHUNKS : 1], b_lds[T::B_CHUNKS];
-    uint32_t a_step = 0, b_step = 0;  // bytes per tile along the contraction
-    if constexpr (T::A_GEN_LDS) {  // generated: chunk = 8 tokens of one sketch column
-#pragma unroll
-        for (int q = 0; q < T::A_CHUNKS; ++q) {
-            const int c = tid + T::THREADS * q, row = c / (BK / 8), kc = c % (BK / 8);
-            a_ok[q] = c < BM * BK / 8;  // uniform per wave
-            a_kk[q] = kc * 8;
-            a_off[q] = (uint32_t)(m0 + row);  // sketch column j
-            a_lds[q] = row * T::A_STRIDE + kchunk_pos<BK>(row, kc) * 8;
-        }
-    } else if constexpr (AMODE == A_KCONTIG) {  // A[m][kk], tile BM x BK
-        a_step = BK * 2;
-#pragma unroll
-        for (int q = 0; q < T::A_CHUNKS; ++q) {
-            const int c = tid + T::THREADS * q, row = c / (BK / 8), kc = c % (BK / 8);
-            a_ok[q] = m0 + row < g.M;
-            a_kk[q] = kc * 8;
-            a_off[q] = (uint32_t)(((m0 + row) * g.lda + kk_begin + kc * 8) * 2);
-            a_lds[q] = row * T::A_STRIDE + kchunk_pos<BK>(row, kc) * 8;
-        }
-    } else if constexpr (AMODE == A_MCONTIG) {  // A stored [kk][m], tile BK x BM
-        a_step = (uint32_t)(BK * g.lda * 2);
-#pragma unroll
-        for (int q = 0; q < T::A_CHUNKS; ++q) {
-            const int c = tid + T::THREADS * q, row = c / (BM / 8), mc = c % (BM / 8);
-            a_ok[q] = m0 + mc * 8 < g.M;
-            a_kk[q] = row;
-            a_off[q] = (uint32_t)(((kk_begin + row) * g.lda + m0 + mc * 8) * 2);
-            a_lds[q] = row * T::A_STRIDE + mc * 8;
-        }
-    }
-    if constexpr (BMODE == B_KCONTIG) {  // B stored [n][kk], tile BN x BK
-        b_step = BK * 2;
-#pragma unroll
-        for (int q = 0; q < T::B_CHUNKS; ++q) {
-            const int c = tid + T::THREADS * q, row = c / (BK / 8), kc = c % (BK / 8);
-            b_ok[q] = n0 + row < g.N;
-            b_kk[q] = kc * 8;
-            b_off[q] = (uint32_t)(((n0 + row) * g.ldb + kk_begin + kc * 8) * 2);
-            b_lds[q] = row * T::B_STRIDE + kchunk_pos<BK>(row, kc) * 8;
-        }
-    } else {  // B stored [kk][n], tile BK x BN
-        b_step = (uint32_t)(BK * g.ldb * 2);
-#pragma unroll
-        for (int q = 0; q < T::B_CHUNKS; ++q) {
-            const int c = tid + T::THREADS * q, row = c / (BN / 8), nc = c % (BN / 8);
-            b_ok[q] = n0 + nc * 8 < g.N;
-            b_kk[q] = row;
-            b_off[q] = (uint32_t)(((kk_begin + row) * g.ldb + n0 + nc * 8) * 2);
-            b_lds[q] = row * T::B_STRIDE + nc * 8;
-        }
-    }
-    const int kk_len = (int)(kk_end - kk_begin);  // contraction elements of this slice (may be <= 0)
-
-    // D register sets hold the tiles in flight: tile t + D is requested while tile t is computed.
-    u32x4_t ra[D][T::A_CHUNKS > 0 ? T::A_CHUNKS : 1], rb[D][T::B_CHUNKS];
-
-    // Work-groups walk the contraction from different starting tiles (and wrap around): with a
-    // power-of-two row pitch all rows of a tile fall on the same one or two L2 channels, and the
-    // rotation spreads concurrently running work-groups over the channels.  The eight tiles of one
-    // band column (same B column block, neighbouring A row blocks) share a starting tile so that
-    // their common operand is fetched once into L2.
-#ifndef RMM_STAGGER_DIV
-#define RMM_STAGGER_DIV 8
-#endif
-    const int stagger = (num_tiles > 0 && RMM_STAGGER_DIV > 0) ? (int)((tile / RMM_STAGGER_DIV) % num_tiles) : 0;
-    auto rotated = [&](int t) { return t + stagger - (t + stagger >= num_tiles ? num_tiles : 0); };
-
-    auto issue = [&](int set, int t_seq) {  // request the t_seq-th tile of this slice into register set `set`
-        const int t = t_seq < num_tiles ? rotated(t_seq) : t_seq;  // past the end: stays out of range, reads zeros
-        const int kk_tile = t * BK;
-        if constexpr (T::A_IN_LDS && !T::A_GEN_LDS) {
-#pragma unroll
-            for (int q = 0; q < T::A_CHUNKS; ++q) {
-                const bool ok = a_ok[q] && kk_tile + a_kk[q] < kk_len;
-                ra[set][q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, ok ? a_off[q] + (uint32_t)t * a_step : OOB,
-                                                                   0, 0);
-            }
-        }
-#pragma unroll
-        for (int q = 0; q < T::B_CHUNKS; ++q) {
-            const bool ok = b_ok[q] && kk_tile + b_kk[q] < kk_len;
-            rb[set][q] =
-                __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, ok ? b_off[q] + (uint32_t)t * b_step : OOB, 0, 0);
-        }
-    };
-
-    // Writes the t_seq-th tile of the slice (held in register set `set`) into LDS stage `stage`.
-    // A generated A tile is made here: every thread produces its 16-byte chunks (8 consecutive
-    // tokens of one sketch column = one Philox call for the Gaussian kind; one byte of the call
-    // that covers the chunk's 128-token block for the Rademacher kind) and stores them where a
-    // loaded K-contiguous tile would go.  A tile past the end is generated too (its B tile is all
-    // zeros), which keeps the step free of branches.
-    auto store_lds = [&](int set, int stage, int t_seq) {
-        bf16_t *As = lds + stage * T::STAGE_ELEMS;
-        bf16_t *Bs = As + T::A_ELEMS;
-        if constexpr (T::A_GEN_LDS) {
-            const int64_t kk_tile = kk_begin + (int64_t)(t_seq < num_tiles ? rotated(t_seq) : 0) * BK;
-#pragma unroll
-            for (int q = 0; q < T::A_CHUNKS; ++q) {
-                if (!a_ok[q]) continue;
-                const int64_t tok = kk_tile + a_kk[q];
-                bf16x8_t v;
-                if constexpr (AMODE == A_GAUSS_LDS) {
-                    v = gauss_operand(g.st, (uint32_t)(tok >> 3), a_off[q]);
-                } else {
-                    const Words4 r = philox4x32_10((uint32_t)(tok >> 7), a_off[q], g.st.off0, g.st.off1, g.st.key0, g.st.key1);
-                    v = radem_operand(r, (uint32_t)tok);
-                }
-                *reinterpret_cast<bf16x8_t *>(As + a_lds[q]) = v;
-            }
-        } else if constexpr (T::A_IN_LDS) {
-#pragma unroll
-            for (int q = 0; q < T::A_CHUNKS; ++q) *reinterpret_cast<u32x4_t *>(As + a_lds[q]) = ra[set][q];
-        }
-#pragma unroll
-        for (int q = 0; q < T::B_CHUNKS; ++q) *reinterpret_cast<u32x4_t *>(Bs + b_lds[q]) = rb[set][q];
-    };
-
-    // Operand fragments of one 16-deep contraction step.
-    struct Frags {
-        bf16x8_t a[T::TM], b[T::TN];
-    };
-    constexpr int KS = BK / 16 / WAVES_K;  // 16-deep contraction steps per tile and wave: kg, kg + WAVES_K, ...
-    static_assert(KS >= 2, "the pipeline needs two contraction steps per tile and wave");
-
-    // Fragments of step `ks` of the tile whose data sits in LDS stage `stage` and whose first
-    // contraction index is kk0.  LDS reads (and the generator's ALU work) issued here run under
-    // the MFMAs of the step before.
-    Words4 rw[T::TM];  // Rademacher: the Philox words of the 128-token block the tile being fetched lies in
-    auto load_frags = [&](Frags &f, int stage, int64_t kk0, int ks_local) {
-        const int ks = ks_local * WAVES_K + kg;  // this wave's ks_local-th step of the tile
-        const bf16_t *As = lds + stage * T::STAGE_ELEMS;
-        const bf16_t *Bs = As + T::A_ELEMS;
-#pragma unroll
-        for (int a = 0; a < T::TM; ++a) {
-            const int row0 = wm * T::WTM + a * 32;
-            if constexpr (T::A_KLAYOUT) {
-                f.a[a] = frag_kcontig<BK>(As, row0, ks * 16, lane);
-            } else if constexpr (AMODE == A_MCONTIG) {
-                f.a[a] = frag_transposed(As, T::A_STRIDE, row0, ks * 16, lane);
-            } else {
-                const uint32_t j = (uint32_t)(m0 + row0 + (lane & 31));
-                const int64_t tok = kk0 + ks * 16 + ((lane >> 5) << 3);  // first of this lane's 8 tokens
-                if constexpr (AMODE == A_GAUSS) {
-                    f.a[a] = gauss_operand(g.st, (uint32_t)(tok >> 3), j);
-                } else {
-                    if (ks_local == 0)  // a tile (BK <= 128 tokens, aligned) never straddles two blocks
-                        rw[a] = philox4x32_10((uint32_t)(kk0 >> 7), j, g.st.off0, g.st.off1, g.st.key0, g.st.key1);
-                    f.a[a] = radem_operand(rw[a], (uint32_t)tok);
-                }
-            }
-        }
-#pragma unroll
-        for (int b = 0; b < T::TN; ++b) {
-            const int col0 = wn * T::WTN + b * 32;
-            if constexpr (BMODE == B_KCONTIG)
-                f.b[b] = frag_kcontig<BK>(Bs, col0, ks * 16, lane);
-            else
-                f.b[b] = frag_transposed(Bs, T::B_STRIDE, col0, ks * 16, lane);
-        }
-    };
-
-    auto multiply = [&](const Frags &f) {
-#pragma unroll
-        for (int a = 0; a < T::TM; ++a)
-#pragma unroll
-            for (int b = 0; b < T::TN; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[b], f.a[a], acc[a][b], 0, 0, 0);
-    };
-
-    // Pipeline.  Global side: tiles t+3 .. t+D-1 are in flight in D register sets (tile u in set
-    // u % D) while tile t is computed; the loop runs over whole groups of D tiles so that every
-    // load's register set is fixed at compile time, and tiles past the end read as zeros.  LDS side:
-    // three stages (tile u in stage u % 3).  During step t tile t+2 is written: its stage was last
-    // read in step t-1, which every wave has left, and it is first read at the end of step t+1,
-    // after the barrier that closes step t+1 ... so ONE barrier per step is enough, and the
-    // fragments of the next 16-deep contraction step are always fetched before the MFMAs of the
-    // current one are issued, also across the tile boundary.
-    static_assert(D >= 3, "tile t+2 must have been requested before step t");
-#ifdef RMM_DEBUG_TRACE
-    unsigned long long *tr = g.trace ? g.trace + ((size_t)blockIdx.x + (size_t)gridDim.x * blockIdx.z) * 64 : nullptr;
-    if (tr && tid == 0) tr[0] = clock64(), tr[62] = wall_clock64();
-#endif
-#pragma unroll
-    for (int s = 0; s < D; ++s) issue(s, s);
-    store_lds(0, 0, 0);
-    store_lds(1, 1, 1);
-    __syncthreads();
-    Frags cur, nxt;
-    load_frags(cur, 0, kk_begin + (int64_t)rotated(0) * BK, 0);
-    const int groups = (num_tiles + D - 1) / D;
-    int st_cur = 0;  // stage of tile t
-#ifdef RMM_DEBUG_TRACE
-    if (tr && tid == 0) tr[1] = clock64();
-#endif
-    for (int grp = 0; grp < groups; ++grp) {
-#pragma unroll
-        for (int s = 0; s < D; ++s) {
-            const int t = grp * D + s;
-            // A step past the end costs little when both operands are loaded (all zeros, no branch);
-            // with a generated operand it would cost a full step of generator work, so leave
-            // (only the last group can be short; the outer loop ends with it).
-            if constexpr (!T::A_IN_LDS || T::A_GEN_LDS)
-                if (t >= num_tiles) break;
-            const int64_t kk_t = kk_begin + (int64_t)(t < num_tiles ? rotated(t) : 0) * BK;
-            const int64_t kk_n = kk_begin + (int64_t)(t + 1 < num_tiles ? rotated(t + 1) : 0) * BK;
-            const int st_next = st_cur == 2 ? 0 : st_cur + 1, st_write = st_next == 2 ? 0 : st_next + 1;
-#ifndef RMM_DEBUG_NOLOAD
-            issue(s, t + D);
-#endif
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                if (ks == KS - 1)
-                    load_frags(nxt, st_next, kk_n, 0);
-                else
-                    load_frags(nxt, st_cur, kk_t, ks + 1);
-                multiply(cur);  // tiles past the end are all zeros: no branch, the step stays one basic block
-                cur = nxt;
-                // Tile t+2 goes to LDS during the second contraction step: its global loads (issued
-                // one tile step earlier) get most of this step as extra time to arrive.  A generated
-                // tile is made during the first one instead, ahead of the step's other ALU work.
-                if (ks == (T::A_GEN_LDS ? 0 : RMM_TUNE_STORE_KS)) store_lds((s + 2) % D, st_write, t + 2);
-            }
-            __builtin_amdgcn_iglp_opt(0);  // ask the scheduler to interleave LDS / global traffic with the MFMAs
-            __syncthreads();
-            st_cur = st_next;
-#ifdef RMM_DEBUG_TRACE
-            if (tr && tid == 0 && t + 2 < 60) tr[t + 2] = clock64();
-#endif
-        }
-    }
-#ifdef RMM_DEBUG_TRACE
-    if (tr && tid == 0) tr[60] = clock64();
-#endif
-
-    // Epilogue.  The MFMA was issued with the operands swapped (B fragment first), so the
-    // accumulators hold C^T tiles: register v of lane l is C(l % 32, 8*(v/4) + 4*(l/32) + v%4)
-    // of its 32x32 tile, i.e. every lane owns four runs of four consecutive columns of one row.
-    // Storing that directly would touch 32 rows with 16 bytes each per instruction; instead every
-    // wave passes a strip of 32 rows x 128 bytes through a private piece of LDS and writes it out
-    // with 16 bytes per lane, 8 lanes per row (full 128-byte lines).
-    __syncthreads();  // all fragment reads of the main loop are done; LDS is free
-    // Two wave groups that split the contraction each end up owning half of the 32x32 tiles of
-    // their (identical) wave tile: a group parks the tiles the other one owns in LDS, 16 bytes per
-    // lane and run with consecutive lanes consecutive, in rounds that fit the LDS, and adds what
-    // the other group parked for it.  Both groups then write their halves.
-    static_assert(WAVES_K <= 2, "the cross-group sum is written for two groups");
-    constexpr int P = T::TM * T::TN;  // tiles per wave, numbered a * TN + b
-    constexpr int OWN = P / WAVES_K;  // group kg owns tiles kg*OWN .. kg*OWN + OWN - 1
-    if constexpr (WAVES_K == 2) {
-        static_assert(P % 2 == 0, "an even number of tiles per wave");
-        constexpr int CH_MAX = T::LDS_BYTES / (64 * T::THREADS);  // tiles per thread and round that fit
-        static_assert(CH_MAX >= 1, "one tile per thread fits in LDS");
-        constexpr int CH = OWN < CH_MAX ? OWN : CH_MAX;
-        float4 *park = reinterpret_cast<float4 *>(lds);
-        constexpr int GROUP_THREADS = T::THREADS / 2;
-        const int partner = kg == 0 ? tid + GROUP_THREADS : tid - GROUP_THREADS;
-        // `first` is a literal at every call, so all accumulator indices are static after unrolling.
-        auto park_tiles = [&](auto first, int c0) {
-#pragma unroll
-            for (int c = 0; c < CH; ++c) {
-                const int p = decltype(first)::value + c0 + c;
-                if (c0 + c < OWN) {
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        park[(c * 4 + q) * T::THREADS + tid] =
-                            make_float4(acc[p / T::TN][p % T::TN][4 * q], acc[p / T::TN][p % T::TN][4 * q + 1],
-                                        acc[p / T::TN][p % T::TN][4 * q + 2], acc[p / T::TN][p % T::TN][4 * q + 3]);
-                }
-            }
-        };
-        auto add_tiles = [&](auto first, int c0) {
-#pragma unroll
-            for (int c = 0; c < CH; ++c) {
-                const int p = decltype(first)::value + c0 + c;
-                if (c0 + c < OWN) {
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const float4 pv = park[(c * 4 + q) * T::THREADS + partner];
-                        acc[p / T::TN][p % T::TN][4 * q] += pv.x, acc[p / T::TN][p % T::TN][4 * q + 1] += pv.y;
-                        acc[p / T::TN][p % T::TN][4 * q + 2] += pv.z, acc[p / T::TN][p % T::TN][4 * q + 3] += pv.w;
-                    }
-                }
-            }
-        };
-        using Zero = std::integral_constant<int, 0>;
-        using Half = std::integral_constant<int, OWN>;
-#pragma unroll
-        for (int c0 = 0; c0 < OWN; c0 += CH) {
-            if (kg == 0)
-                park_tiles(Half(), c0);  // group 0 gives away the upper half
-            else
-                park_tiles(Zero(), c0);
-            __syncthreads();
-            if (kg == 0)
-                add_tiles(Zero(), c0);
-            else
-                add_tiles(Half(), c0);
-            __syncthreads();
-        }
-    }
-    if constexpr (OUT == OUT_SUMSQ) {
-        // Squared Frobenius norm of the tile: rows and columns beyond the matrix were loaded as
-        // zeros, so they add nothing.  Per-lane sums, wave reduction, then the waves' sums in fp64.
-        float sq = 0.0f;
-#pragma unroll
-        for (int a = 0; a < T::TM; ++a)
-#pragma unroll
-            for (int b = 0; b < T::TN; ++b) {
-                if (WAVES_K > 1 && (a * T::TN + b) / OWN != kg) continue;  // the other group's tiles
-#pragma unroll
-                for (int v = 0; v < 16; ++v) sq += acc[a][b][v] * acc[a][b][v];
-            }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) sq += __shfl_xor(sq, off, 64);
-        double *red = reinterpret_cast<double *>(lds);
-        if (lane == 0) red[wave] = (double)sq;
-        __syncthreads();
-        if (tid == 0) {
-            double t = 0.0;
-#pragma unroll
-            for (int w = 0; w < T::THREADS / 64; ++w) t += red[w];
-            reinterpret_cast<double *>(g.C)[blockIdx.x] = t;
-        }
+template <typename S, int AMODE, int BMODE, int OUT>
+hipError_t launch(const GemmArgs &g, int splits, hipStream_t stream) {
+    const int64_t tiles = ((g.M + S::BM - 1) / S::BM) * ((g.N + S::BN - 1) / S::BN);
+    const dim3 grid((unsigned)tiles, 1, (unsigned)splits);
+    if constexpr (AMODE >= A_GAUSS || std::is_same<S, ShapeLarge>::value) {
+        gemm_mfma_kernel<S, AMODE, BMODE, OUT, 3><<<grid, S::THREADS, 0, stream>>>(g);
     } else {
-        constexpr int EB = OUT == OUT_BF16 ? 2 : 4;         // bytes per output element
-        constexpr int CW = 128 / EB;                         // columns per strip: 64 (bf16) or 32 (fp32)
-        constexpr int TPS = CW / 32;                         // 32-column MFMA tiles per strip
-        constexpr int PITCH = 128 + 16;                      // bytes per strip row in LDS
-        static_assert(T::THREADS / 64 * 32 * PITCH <= T::LDS_BYTES, "staging area fits in LDS");
-        static_assert(WAVES_K == 1 || (OWN % TPS == 0 && T::TN % TPS == 0), "no strip straddles the two groups' tiles");
-        char *stage = reinterpret_cast<char *>(lds) + wave * 32 * PITCH;
-        const int r = lane & 31, h = lane >> 5;
-#pragma unroll
-        for (int a = 0; a < T::TM; ++a) {
-            const int64_t row0 = m0 + wm * T::WTM + a * 32;
-#pragma unroll
-            for (int b0 = 0; b0 < T::TN; b0 += TPS) {
-                if (WAVES_K > 1 && (a * T::TN + b0) / OWN != kg) continue;  // the other group's tiles
-                const int64_t col0 = n0 + wn * T::WTN + b0 * 32;
-#pragma unroll
-                for (int bb = 0; bb < TPS; ++bb) {
-                    if (b0 + bb >= T::TN) break;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        float v[4];
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) v[u] = acc[a][b0 + bb][4 * q + u];
-                        const int c = bb * 32 + 8 * q + 4 * h;  // column inside the strip
-                        if constexpr (OUT == OUT_BF16) {
-#pragma unroll
-                            for (int u = 0; u < 4; ++u) v[u] *= g.alpha;
-                            if (g.accumulate && row0 + r < g.M && col0 + c < g.N) {  // N is a multiple of 8
-                                const uint2 cv = *reinterpret_cast<const uint2 *>(reinterpret_cast<const bf16_t *>(g.C) +
-                                                                                  (row0 + r) * g.ldc + col0 + c);
-                                v[0] += __uint_as_float(cv.x << 16);
-                                v[1] += __uint_as_float(cv.x & 0xFFFF0000u);
-                                v[2] += __uint_as_float(cv.y << 16);
-                                v[3] += __uint_as_float(cv.y & 0xFFFF0000u);
-                            }
-                            if (g.bias != nullptr && col0 + c < g.N) {
-                                const uint2 bv = *reinterpret_cast<const uint2 *>(g.bias + col0 + c);
-                                v[0] += __uint_as_float(bv.x << 16);
-                                v[1] += __uint_as_float(bv.x & 0xFFFF0000u);
-                                v[2] += __uint_as_float(bv.y << 16);
-                                v[3] += __uint_as_float(bv.y & 0xFFFF0000u);
-                            }
-                            union {
-                                bf16x2_t hh[2];
-                                uint2 u;
-                            } o;
-                            o.hh[0] = __builtin_convertvector((f32x2_t){v[0], v[1]}, bf16x2_t);  // nearest even
-                            o.hh[1] = __builtin_convertvector((f32x2_t){v[2], v[3]}, bf16x2_t);
-                            *reinterpret_cast<uint2 *>(stage + r * PITCH + c * 2) = o.u;
-                        } else {
-                            *reinterpret_cast<float4 *>(stage + r * PITCH + c * 4) = make_float4(v[0], v[1], v[2], v[3]);
-                        }
-                    }
-                }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                // read back: lane l takes 16 bytes: chunk (l % 8) of row (l / 8) + 8*i
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int rr = (lane >> 3) + 8 * i, ch = lane & 7;
-                    const uint4 d = *reinterpret_cast<const uint4 *>(stage + rr * PITCH + ch * 16);
-                    const int64_t row = row0 + rr, col = col0 + ch * (16 / EB);
-#ifdef RMM_DEBUG_NOEPI
-                    if (g.alpha != 123.0f) continue;
-#endif
-                    if (row >= g.M || col >= g.N || ch * (16 / EB) >= (T::TN - b0) * 32) continue;
-                    if constexpr (OUT == OUT_BF16)
-                        *reinterpret_cast<uint4 *>(reinterpret_cast<bf16_t *>(g.C) + row * g.ldc + col) = d;
-                    else
-                        *reinterpret_cast<uint4 *>(reinterpret_cast<float *>(g.C) +
-                                                   (int64_t)blockIdx.z * g.split_stride + row * g.ldc + col) = d;
-                }
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-            }
-        }
+        if (plain_depth(g.K < g.k_chunk ? g.K : g.k_chunk, S::BK) == 4)
+            gemm_mfma_kernel<S, AMODE, BMODE, OUT, 4><<<grid, S::THREADS, 0, stream>>>(g);
+        else
+            gemm_mfma_kernel<S, AMODE, BMODE, OUT, 3><<<grid, S::THREADS, 0, stream>>>(g);
     }
-#ifdef RMM_DEBUG_TRACE
-    if (tr && tid == 0) tr[63] = clock64(), tr[61] = wall_clock64();
-#endif
+    return hipGetLastError();
 }
 
-// out[r][c] (bf16) = alpha * sum_s part[s][r][c]; 8 columns per thread.
-__global__ void __launch_bounds__(256) reduce_partials_kernel(const float *__restrict__ part, bf16_t *__restrict__ out,
-                                                              int64_t elems, int splits, int64_t split_stride,
-                                                              float alpha) {
-    const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
-    if (e >= elems) return;
-    float4 s = *reinterpret_cast<const float4 *>(part + e);
-    int z = 1;
-    for (; z + 7 < splits; z += 8) {  // eight loads in flight, added in slice order
-        float4 p[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) p[u] = *reinterpret_cast<const float4 *>(part + (int64_t)(z + u) * split_stride + e);
-#pragma unroll
-        for (int u = 0; u < 8; ++u) s.x += p[u].x, s.y += p[u].y, s.z += p[u].z, s.w += p[u].w;
-    }
-    for (; z + 3 < splits; z += 4) {
-        float4 p[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) p[u] = *reinterpret_cast<const float4 *>(part + (int64_t)(z + u) * split_stride + e);
-#pragma unroll
-        for (int u = 0; u < 4; ++u) s.x += p[u].x, s.y += p[u].y, s.z += p[u].z, s.w += p[u].w;
-    }
-    for (; z < splits; ++z) {
-        const float4 p = *reinterpret_cast<const float4 *>(part + (int64_t)z * split_stride + e);
-        s.x += p.x, s.y += p.y, s.z += p.z, s.w += p.w;
-    }
-    uint2 o;
-    o.x = (uint32_t)f32_to_bf16(alpha * s.x) | ((uint32_t)f32_to_bf16(alpha * s.y) << 16);
-    o.y = (uint32_t)f32_to_bf16(alpha * s.z) | ((uint32_t)f32_to_bf16(alpha * s.w) << 16);
-    *reinterpret_cast<uint2 *>(out + e) = o;
+int64_t tiles_of(int64_t m, int64_t n, int64_t bm, int64_t bn) { return ((m + bm - 1) / bm) * ((n + bn - 1) / bn); }
+
+// Tile shape of a plain product with an m x n output and contraction kk.
+//   256 x 256 (8 waves, one work-group per compute unit) once there are at least 160 such tiles:
+//     half the operand traffic per flop of the 128 x 128 tile, which needs more bytes per clock
+//     from L2 than it delivers at full MFMA rate;
+//   64 x 64 when there are fewer than 65 tiles of 128 x 128 (a quarter of the compute units);
+//   128 x 128 x 64 with two wave groups splitting the contraction when there are at most 256
+//     tiles and the contraction is 1536 or longer (a compute unit then still holds 8 waves);
+//   128 x 128 x 32 with 4 waves otherwise (two work-groups per compute unit).
+int gemm_cfg(int64_t m, int64_t n, int64_t kk) {
+    if (tiles_of(m, n, ShapeLarge::BM, ShapeLarge::BN) >= 160) return GEMM_LARGE;
+    const int64_t t128 = tiles_of(m, n, 128, 128);
+    if (t128 < 65) return GEMM_TINY;
+    if (t128 <= 256 && kk >= 1536) return GEMM_SPLIT;
+    return GEMM_MID;
 }
 
-// ---------------------------------------------------------------------------------------------
-// Small sketch sizes (k <= 64): S^T A is bound by reading A once from HBM, so this kernel is a
-// streaming pass.  A work-group owns 256 columns and one slice of tokens and walks the slice 64
-// tokens at a time (global -> registers, D steps in flight -> LDS, two stages).  The four waves
-// split the contraction: wave w takes tokens 16w .. 16w+15 of every step, for all 32*TM sketch
-// columns and all 256 operand columns, so every sketch entry is generated exactly once per
-// work-group and the generator's ALU work stays far below the memory time.  At the end the four
-// partial accumulators are summed through LDS and written as fp32 partials of the slice (or,
-// with a single slice, scaled and rounded to bf16).
-struct SmallkArgs {
-    const bf16_t *A;  // n x d
-    void *C;          // bf16 k x d, or fp32 partials [slice][k][d]
-    int64_t n, d, k;
-    int64_t a_bytes;
-    int64_t k_chunk;  // tokens per slice (multiple of 128)
-    float alpha;
-    SketchState st;
-#ifdef RMM_DEBUG_TRACE
-    unsigned long long *trace;
-#endif
+template <int AMODE, int BMODE, int OUT>
+hipError_t launch_gemm(int cfg, const GemmArgs &g, hipStream_t stream) {
+    if (cfg == GEMM_LARGE) return launch<ShapeLarge, AMODE, BMODE, OUT>(g, 1, stream);
+    if (cfg == GEMM_SPLIT) return launch<ShapeSplit, AMODE, BMODE, OUT>(g, 1, stream);
+    if constexpr (OUT == OUT_BF16)
+        if (cfg == GEMM_TINY) return launch<ShapeTiny, AMODE, BMODE, OUT>(g, 1, stream);
+    return launch<ShapeMid, AMODE, BMODE, OUT>(g, 1, stream);
+}
+
+GemmArgs args_nt(const bf16_t *X, const bf16_t *W, const bf16_t *bias, bf16_t *Y, int64_t n, int64_t d_in, int64_t d_out) {
+    GemmArgs g{};
+    g.A = X, g.lda = d_in, g.B = W, g.ldb = d_in, g.C = Y, g.ldc = d_out, g.bias = bias;
+    g.M = n, g.N = d_out, g.K = d_in, g.alpha = 1.0f, g.k_chunk = (d_in + 127) / 128 * 128;
+    g.a_bytes = n * d_in * 2, g.b_bytes = d_out * d_in * 2;
+    return g;
+}
+
+GemmArgs args_nn(const bf16_t *dY, const bf16_t *W, bf16_t *dX, int64_t n, int64_t d_in, int64_t d_out) {
+    GemmArgs g{};
+    g.A = dY, g.lda = d_out, g.B = W, g.ldb = d_in, g.C = dX, g.ldc = d_in, g.bias = nullptr;
+    g.M = n, g.N = d_in, g.K = d_out, g.alpha = 1.0f, g.k_chunk = (d_out + 127) / 128 * 128;
+    g.a_bytes = n * d_out * 2, g.b_bytes = d_out * d_in * 2;
+    return g;
+}
+
+// Which kernel serves a sketch product with k > 64 and how its token dimension is cut.
+//   d >= 1024:               the work-group generates the 128 x 32 sketch tile into LDS and all
+//                            eight waves read it, 512 columns per tile (an entry is generated once
+//                            per 512 columns); 64-row tiles for k <= 512 (k = 410 pads to 448 rows
+//                            instead of 512);
+//   d a multiple of 384:     the same with 384-column tiles (d = 768);
+//   other d below 1024:      128 x 256 tiles whose sketch fragments are generated in registers.
+// Tokens are cut into `splits` slices of `k_chunk` tokens (a multiple of 128) so that about 256
+// work-groups exist; with more than one slice the kernel writes fp32 partial results to workspace
+// and reduce_partials_kernel sums them in slice order.
+struct SketchPlan {
+    int cfg, splits;
+    int64_t k_chunk, tiles;
 };
 
-template <int TM, int KIND, int D, int OUT>
-__global__ void __launch_bounds__(256) sketch_smallk_kernel(SmallkArgs g) {
-    constexpr int BN = 256, BK = 64, STRIDE = BN + TPAD, STAGE_ELEMS = BK * STRIDE, CHUNKS = BN * BK / 8 / 256;
-    constexpr int TN = BN / 32;
-    __shared__ __attribute__((aligned(16))) bf16_t lds[2 * STAGE_ELEMS];
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int64_t n0 = (int64_t)blockIdx.x * BN;
-    const int64_t kk_begin = (int64_t)blockIdx.y * g.k_chunk;
-    const int kk_len = (int)(min(g.n, kk_begin + g.k_chunk) - kk_begin);  // >= 1: the host makes no empty slice
-    const int num_tiles = (kk_len + BK - 1) / BK;
-
-    const __amdgpu_buffer_rsrc_t rsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(g.A), (short)0, (int)g.a_bytes, 0x00020000);
-    constexpr uint32_t OOB = 0x80000000u;
-    uint32_t off[CHUNKS];
-    int row_of[CHUNKS], lds_of[CHUNKS];
-#pragma unroll
-    for (int q = 0; q < CHUNKS; ++q) {
-        const int c = tid + 256 * q, row = c / (BN / 8), nc = c % (BN / 8);
-        row_of[q] = row, lds_of[q] = row * STRIDE + nc * 8;
-        off[q] = n0 + nc * 8 < g.d ? (uint32_t)(((kk_begin + row) * g.d + n0 + nc * 8) * 2) : OOB;
-    }
-    const uint32_t step_bytes = (uint32_t)(BK * g.d * 2);
-
-    u32x4_t rb[D][CHUNKS];
-    auto issue = [&](int set, int t) {
-#pragma unroll
-        for (int q = 0; q < CHUNKS; ++q) {
-            const bool ok = t * BK + row_of[q] < kk_len;  // also false for every t >= num_tiles
-            rb[set][q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, ok ? off[q] + (uint32_t)t * step_bytes : OOB, 0, 0);
-        }
-    };
-    auto store_lds = [&](int set, int stage) {
-#pragma unroll
-        for (int q = 0; q < CHUNKS; ++q)
-            *reinterpret_cast<u32x4_t *>(lds + stage * STAGE_ELEMS + lds_of[q]) = rb[set][q];
-    };
-
-    f32x16_t acc[TM][TN];
-#pragma unroll
-    for (int a = 0; a < TM; ++a)
-#pragma unroll
-        for (int b = 0; b < TN; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
-
-#ifdef RMM_DEBUG_TRACE
-    unsigned long long *tr = g.trace ? g.trace + ((size_t)blockIdx.x + (size_t)gridDim.x * blockIdx.y) * 64 : nullptr;
-    if (tr && tid == 0) tr[0] = clock64(), tr[62] = wall_clock64();
-#endif
-#pragma unroll
-    for (int s = 0; s < D; ++s) issue(s, s);
-    store_lds(0, 0);
-    __syncthreads();
-#ifdef RMM_DEBUG_TRACE
-    if (tr && tid == 0) tr[1] = clock64();
-#endif
-    const int groups = (num_tiles + D - 1) / D;
-    for (int grp = 0; grp < groups; ++grp) {
-#pragma unroll
-        for (int s = 0; s < D; ++s) {
-            const int t = grp * D + s;
-#ifdef RMM_DEBUG_TRACE
-            if (tr && tid == 0 && t > 0 && t + 1 < 60) tr[t + 1] = clock64();
-#endif
-            issue(s, t + D);
-            if (t < num_tiles) {
-                const bf16_t *Bs = lds + (t & 1) * STAGE_ELEMS;
-                const int tok = (int)kk_begin + t * BK + 16 * wave + ((lane >> 5) << 3);  // this lane's first token
-                bf16x8_t af[TM], bfr[TN];
-#pragma unroll
-                for (int a = 0; a < TM; ++a) {
-                    const uint32_t j = (uint32_t)(a * 32 + (lane & 31));
-                    if constexpr (KIND == 0) {
-                        af[a] = gauss_operand(g.st, (uint32_t)(tok >> 3), j);
-                    } else {
-                        const Words4 rw =
-                            philox4x32_10((uint32_t)(tok >> 7), j, g.st.off0, g.st.off1, g.st.key0, g.st.key1);
-                        af[a] = radem_operand(rw, (uint32_t)tok);
-                    }
-                }
-#pragma unroll
-                for (int b = 0; b < TN; ++b) bfr[b] = frag_transposed(Bs, STRIDE, b * 32, 16 * wave, lane);
-#pragma unroll
-                for (int a = 0; a < TM; ++a)
-#pragma unroll
-                    for (int b = 0; b < TN; ++b)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[b], af[a], acc[a][b], 0, 0, 0);
-            }
-            store_lds((s + 1) % D, (t + 1) & 1);
-            __syncthreads();  // step t is consumed everywhere, step t+1 is visible
-        }
-    }
-
-#ifdef RMM_DEBUG_TRACE
-    if (tr && tid == 0) tr[60] = clock64();
-#endif
-    // Sum the four waves' accumulators, 32 rows x 128 columns at a time: every wave puts its block
-    // into its own LDS region, then all threads add the four regions and write full rows.
-    // (Accumulator register v of lane l is C(l % 32, 8*(v/4) + 4*(l/32) + v%4) of a 32x32 tile.)
-    constexpr int PITCH = 128 * 4 + 16;  // bytes per row of a region
-    static_assert(4 * 32 * PITCH <= 2 * STAGE_ELEMS * 2, "reduction regions fit in LDS");
-    char *region = reinterpret_cast<char *>(lds);
-    const int r = lane & 31, h = lane >> 5;
-#pragma unroll
-    for (int a = 0; a < TM; ++a)
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-#pragma unroll
-            for (int bb = 0; bb < 4; ++bb)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const f32x16_t &t = acc[a][half * 4 + bb];
-                    *reinterpret_cast<float4 *>(region + (wave * 32 + r) * PITCH + (bb * 32 + 8 * q + 4 * h) * 4) =
-                        make_float4(t[4 * q], t[4 * q + 1], t[4 * q + 2], t[4 * q + 3]);
-                }
-            __syncthreads();
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int f = tid + 256 * i, row = f >> 5, c4 = f & 31;
-                float4 s = *reinterpret_cast<const float4 *>(region + row * PITCH + c4 * 16);
-#pragma unroll
-                for (int w = 1; w < 4; ++w) {
-                    const float4 p = *reinterpret_cast<const float4 *>(region + (w * 32 + row) * PITCH + c4 * 16);
-                    s.x += p.x, s.y += p.y, s.z += p.z, s.w += p.w;
-                }
-                const int64_t grow = a * 32 + row, gcol = n0 + half * 128 + c4 * 4;
-                if (grow < g.k && gcol < g.d) {  // d is a multiple of 4
-                    if constexpr (OUT == OUT_BF16) {
-                        union {
-                            bf16x2_t hh[2];
-                            uint2 u;
-                        } o;
-                        o.hh[0] = __builtin_convertvector((f32x2_t){g.alpha * s.x, g.alpha * s.y}, bf16x2_t);
-                        o.hh[1] = __builtin_convertvector((f32x2_t){g.alpha * s.z, g.alpha * s.w}, bf16x2_t);
-                        *reinterpret_cast<uint2 *>(reinterpret_cast<bf16_t *>(g.C) + grow * g.d + gcol) = o.u;
-                    } else {
-                        *reinterpret_cast<float4 *>(reinterpret_cast<float *>(g.C) +
-                                                    ((int64_t)blockIdx.y * g.k + grow) * g.d + gcol) = s;
-                    }
-                }
-            }
-            __syncthreads();
-        }
-#ifdef RMM_DEBUG_TRACE
-    if (tr && tid == 0) tr[63] = clock64(), tr[61] = wall_clock64();
-#endif
+SketchPlan plan_sketch(int64_t n, int64_t d, int64_t k) {
+    SketchPlan p;
+    const bool rows64 = k <= 512;
+    p.cfg = d >= 1024 ? (rows64 ? SK_WIDE64 : SK_WIDE) : d % 384 == 0 ? (rows64 ? SK_MID64 : SK_MID) : SK_NARROW;
+    const int64_t bm = (p.cfg == SK_WIDE64 || p.cfg == SK_MID64) ? 64 : 128;
+    const int64_t bn = p.cfg == SK_NARROW ? 256 : (p.cfg == SK_MID64 || p.cfg == SK_MID) ? 384 : 512;
+    p.tiles = tiles_of(k, d, bm, bn);
+    const int64_t blocks = (n + 127) / 128;
+    int64_t s = 256 / p.tiles;
+    if (s > blocks) s = blocks;
+    if (s > 64) s = 64;
+    if (s < 1) s = 1;
+    p.k_chunk = (blocks + s - 1) / s * 128;
+    p.splits = (int)((n + p.k_chunk - 1) / p.k_chunk);
+    return p;
 }
 
-// Prefetch depths (register sets of tiles in flight) to choose from.
-#ifndef RMM_TUNE_D1
-#define RMM_TUNE_D1 4
-#endif
-#ifndef RMM_TUNE_D2
-#define RMM_TUNE_D2 3
-#endif
-#ifndef RMM_TUNE_SK_D
-#define RMM_TUNE_SK_D 3
-#endif
-
-#ifdef RMM_DEBUG_TRACE
-unsigned long long *g_trace = nullptr;
-#endif
-#ifndef RMM_TUNE_LARGE
-#define RMM_TUNE_LARGE 256, 256, 32, 2, 4, 1
-#endif
-#ifndef RMM_TUNE_LARGE_BM
-#define RMM_TUNE_LARGE_BM 256
-#endif
-#ifndef RMM_TUNE_LARGE_BN
-#define RMM_TUNE_LARGE_BN 256
-#endif
-#ifndef RMM_TUNE_SPLIT_MIN_K
-#define RMM_TUNE_SPLIT_MIN_K 1536
-#endif
-#ifndef RMM_TUNE_TINY_FIRST
-#define RMM_TUNE_TINY_FIRST 1
-#endif
-#ifndef RMM_TUNE_TINY_MAX_TILES
-#define RMM_TUNE_TINY_MAX_TILES 65
-#endif
-#ifndef RMM_TUNE_LARGE_MIN_TILES
-#define RMM_TUNE_LARGE_MIN_TILES 160
-#endif
-
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int WAVES_K, int AMODE, int BMODE, int OUT>
-hipError_t launch(const GemmArgs &g_in, int splits, hipStream_t stream) {
-    GemmArgs g = g_in;
-#ifdef RMM_DEBUG_TRACE
-    g.trace = (AMODE == RMM_DEBUG_TRACE_A && BMODE == RMM_DEBUG_TRACE_B) ? g_trace : nullptr;
-#endif
-    const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-    dim3 grid((unsigned)tiles, 1, (unsigned)splits);
-    // The kernel runs whole groups of D tiles; take the depth that wastes fewer.
-    const int64_t kt = (min(g.K, g.k_chunk) + BK - 1) / BK;
-    if constexpr (AMODE >= A_GAUSS) {
-        // The sketch kernels load one operand only and need their registers for wide wave tiles.
-        gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, WAVES_K, AMODE, BMODE, OUT, RMM_TUNE_SK_D>
-            <<<grid, 64 * WAVES_M * WAVES_N * WAVES_K, 0, stream>>>(g);
-        return hipGetLastError();
+GemmArgs args_sketch(const bf16_t *A, int64_t n, int64_t d, int64_t k, SketchState st, const SketchPlan &p, bf16_t *out,
+                     void *ws) {
+    GemmArgs g{};
+    g.A = nullptr, g.lda = 0, g.B = A, g.ldb = d, g.bias = nullptr;
+    g.M = k, g.N = d, g.K = n, g.st = st, g.ldc = d, g.k_chunk = p.k_chunk;
+    g.a_bytes = 0, g.b_bytes = n * d * 2;
+    if (p.splits == 1) {
+        g.C = out, g.alpha = 1.0f / sqrtf((float)k);
+    } else {
+        g.C = ws, g.alpha = 1.0f, g.split_stride = k * d;
     }
-    const int64_t pad1 = (kt + RMM_TUNE_D1 - 1) / RMM_TUNE_D1 * RMM_TUNE_D1 - kt;
-    const int64_t pad2 = (kt + RMM_TUNE_D2 - 1) / RMM_TUNE_D2 * RMM_TUNE_D2 - kt;
-    if (pad1 <= pad2)
-        gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, WAVES_K, AMODE, BMODE, OUT, RMM_TUNE_D1>
-            <<<grid, 64 * WAVES_M * WAVES_N * WAVES_K, 0, stream>>>(g);
+    return g;
+}
+
+template <int OUT>
+hipError_t launch_sketch_cfg(int cfg, int kind, const GemmArgs &g, int splits, hipStream_t stream) {
+    switch (cfg) {
+        case SK_WIDE:
+            return kind == 0 ? launch<ShapeSkWide, A_GAUSS_LDS, B_NCONTIG, OUT>(g, splits, stream)
+                             : launch<ShapeSkWide, A_RADEM_LDS, B_NCONTIG, OUT>(g, splits, stream);
+        case SK_WIDE64:
+            return kind == 0 ? launch<ShapeSkWide64, A_GAUSS_LDS, B_NCONTIG, OUT>(g, splits, stream)
+                             : launch<ShapeSkWide64, A_RADEM_LDS, B_NCONTIG, OUT>(g, splits, stream);
+        case SK_MID64:
+            return kind == 0 ? launch<ShapeSkMid64, A_GAUSS_LDS, B_NCONTIG, OUT>(g, splits, stream)
+                             : launch<ShapeSkMid64, A_RADEM_LDS, B_NCONTIG, OUT>(g, splits, stream);
+        case SK_MID:
+            return kind == 0 ? launch<ShapeSkMid, A_GAUSS_LDS, B_NCONTIG, OUT>(g, splits, stream)
+                             : launch<ShapeSkMid, A_RADEM_LDS, B_NCONTIG, OUT>(g, splits, stream);
+        default:
+            return kind == 0 ? launch<ShapeSkNarrow, A_GAUSS, B_NCONTIG, OUT>(g, splits, stream)
+                             : launch<ShapeSkNarrow, A_RADEM, B_NCONTIG, OUT>(g, splits, stream);
+    }
+}
+
+hipError_t launch_reduce(const void *ws, bf16_t *out, int64_t k, int64_t d, int splits, hipStream_t stream) {
+    const int64_t elems = k * d;  // d % 8 == 0, so elems % 4 == 0
+    reduce_partials_kernel<<<(unsigned)((elems / 4 + 255) / 256), 256, 0, stream>>>((const float *)ws, out, elems, splits,
+                                                                                     elems, 1.0f / sqrtf((float)k));
+    return hipGetLastError();
+}
+
+// The streaming kernel of small sketch sizes: 256-column work-groups, token slices so that about
+// one work-group per compute unit exists; 4 register sets of loads in flight.
+constexpr int64_t kSmallK = 64;
+int smallk_slices(int64_t n, int64_t d, int64_t *k_chunk) {
+    const int64_t col_tiles = (d + 255) / 256, blocks = (n + 127) / 128;
+    int64_t s = 256 / col_tiles;
+    if (s > blocks) s = blocks;
+    if (s < 1) s = 1;
+    *k_chunk = (blocks + s - 1) / s * 128;
+    return (int)((n + *k_chunk - 1) / *k_chunk);
+}
+
+template <int TM, int KIND>
+hipError_t launch_smallk(const SmallkArgs &g, int slices, hipStream_t stream) {
+    const dim3 grid((unsigned)((g.d + 255) / 256), (unsigned)slices);
+    if (slices == 1)
+        sketch_smallk_kernel<TM, KIND, 4, OUT_BF16><<<grid, 256, 0, stream>>>(g);
     else
-        gemm_mfma_kernel<BM, BN, BK, WAVES_M, WAVES_N, WAVES_K, AMODE, BMODE, OUT, RMM_TUNE_D2>
-            <<<grid, 64 * WAVES_M * WAVES_N * WAVES_K, 0, stream>>>(g);
+        sketch_smallk_kernel<TM, KIND, 4, OUT_F32_PARTIAL><<<grid, 256, 0, stream>>>(g);
     return hipGetLastError();
 }
 
-// Large outputs: 256x256 tiles (half the operand traffic per flop), one work-group per compute
-// unit, prefetch depth 3.  Worth it once there is at least one such tile per compute unit.
-template <int AMODE, int BMODE, int OUT = OUT_BF16>
-hipError_t launch_large(const GemmArgs &g_in, hipStream_t stream) {
-    GemmArgs g = g_in;
-#ifdef RMM_DEBUG_TRACE
-    g.trace = (AMODE == RMM_DEBUG_TRACE_A && BMODE == RMM_DEBUG_TRACE_B) ? g_trace : nullptr;
-#endif
-    const int64_t tiles = ((g.M + RMM_TUNE_LARGE_BM - 1) / RMM_TUNE_LARGE_BM) * ((g.N + RMM_TUNE_LARGE_BN - 1) / RMM_TUNE_LARGE_BN);
-    typedef Tile<RMM_TUNE_LARGE, AMODE, BMODE, OUT> T;
-    gemm_mfma_kernel<RMM_TUNE_LARGE, AMODE, BMODE, OUT, 3><<<dim3((unsigned)tiles), T::THREADS, 0, stream>>>(g);
-    return hipGetLastError();
-}
+// Brackets a kernel with the caller's events (either may be null: nothing is recorded).
+struct EventPair {
+    hipEvent_t begin, end;
+    hipStream_t stream;
+    EventPair(hipEvent_t b, hipEvent_t e, hipStream_t s) : begin(b), end(e), stream(s) {
+        if (begin != nullptr && end != nullptr) (void)hipEventRecord(begin, stream);
+    }
+    void done() {
+        if (begin != nullptr && end != nullptr) (void)hipEventRecord(end, stream);
+        begin = end = nullptr;
+    }
+    ~EventPair() { done(); }
+};
 
-bool large_tiles_pay(int64_t m, int64_t n) {
-    return ((m + RMM_TUNE_LARGE_BM - 1) / RMM_TUNE_LARGE_BM) * ((n + RMM_TUNE_LARGE_BN - 1) / RMM_TUNE_LARGE_BN) >=
-           RMM_TUNE_LARGE_MIN_TILES;
-}
-
-// Few 128x128 tiles (at most one per compute unit) and a long contraction: two wave groups per
-// tile split the contraction, so that a compute unit still holds eight waves.
-// Very small outputs (fewer 128x128 tiles than a quarter of the compute units): 64x64 tiles.
-bool tiny_tiles_pay(int64_t m, int64_t n) { return ((m + 127) / 128) * ((n + 127) / 128) < RMM_TUNE_TINY_MAX_TILES; }
-
-bool split_waves_pay(int64_t m, int64_t n, int64_t kk) {
-    return ((m + 127) / 128) * ((n + 127) / 128) <= 256 && kk >= RMM_TUNE_SPLIT_MIN_K;
+// The paired launch exists for a plain product on 256 x 256 tiles, or (dX only) on the
+// 128 x 128 x 64 split tiles at prefetch depth 4, next to a sketch product with an LDS-generated
+// tile and at least two token slices.
+bool pair_ok(int cfg_a, int depth_a, const SketchPlan &p, bool nn) {
+    if (p.cfg == SK_NARROW || p.splits < 2) return false;
+    if (cfg_a == GEMM_LARGE) return true;
+    return nn && cfg_a == GEMM_SPLIT && depth_a == 4;
 }
 
 }  // namespace
-
-// Tile shapes: BM, BN, BK, waves along M, waves along N, wave groups along the contraction.
-#ifndef RMM_TUNE_NT
-#define RMM_TUNE_NT 128, 128, 32, 2, 2, 1
-#endif
-#ifndef RMM_TUNE_NN
-#define RMM_TUNE_NN 128, 128, 32, 2, 2, 1
-#endif
-#ifndef RMM_TUNE_DW
-#define RMM_TUNE_DW 128, 128, 32, 2, 2, 1
-#endif
-#ifndef RMM_TUNE_TINY
-#define RMM_TUNE_TINY 64, 64, 32, 2, 2, 1
-#endif
-#ifndef RMM_TUNE_SPLIT
-#define RMM_TUNE_SPLIT 128, 128, 64, 2, 2, 2
-#endif
-#ifndef RMM_TUNE_SK
-#define RMM_TUNE_SK 128, 256, 64, 4, 1, 2
-#endif
-// Wide operands (d >= RMM_TUNE_SK_WIDE_MIN_D): the sketch tile is generated once per work-group
-// into LDS and shared by all waves, 512 columns per tile.
-#ifndef RMM_TUNE_SKW
-#define RMM_TUNE_SKW 128, 512, 32, 2, 4, 1
-#endif
-#ifndef RMM_TUNE_SKW_BM
-#define RMM_TUNE_SKW_BM 128
-#endif
-#ifndef RMM_TUNE_SKW_BN
-#define RMM_TUNE_SKW_BN 512
-#endif
-#ifndef RMM_TUNE_SK_ROWS64_MAX_K
-#define RMM_TUNE_SK_ROWS64_MAX_K 512
-#endif
-#ifndef RMM_TUNE_SK_WIDE_MIN_D
-#define RMM_TUNE_SK_WIDE_MIN_D 1024
-#endif
-#ifndef RMM_TUNE_SK_BM
-#define RMM_TUNE_SK_BM 128
-#define RMM_TUNE_SK_BN 256
-#endif
-#ifndef RMM_TUNE_SK_WGS
-#define RMM_TUNE_SK_WGS 256
-#endif
-// Streaming kernel for k <= 64: work-groups aimed at, prefetch depth for k <= 32 and for k <= 64.
-#ifndef RMM_TUNE_SMALLK_WGS
-#define RMM_TUNE_SMALLK_WGS 256
-#endif
-#ifndef RMM_TUNE_SMALLK_D1
-#define RMM_TUNE_SMALLK_D1 4
-#endif
-#ifndef RMM_TUNE_SMALLK_D2
-#define RMM_TUNE_SMALLK_D2 4
-#endif
-
-#ifdef RMM_DEBUG_TRACE
-extern "C" void rmm_debug_set_trace(void *p) { g_trace = (unsigned long long *)p; }
-#endif
 
 bool mfma_shape_ok(int64_t n, int64_t d_in, int64_t d_out, int64_t k) {
     // 16-byte chunks need widths that are multiples of 8; buffer loads need operands below 2^31 bytes.
@@ -990,28 +203,14 @@ bool mfma_shape_ok(int64_t n, int64_t d_in, int64_t d_out, int64_t k) {
 
 hipError_t launch_linear_nt_bf16(const bf16_t *X, const bf16_t *W, const bf16_t *bias, bf16_t *Y, int64_t n,
                                  int64_t d_in, int64_t d_out, hipStream_t stream) {
-    GemmArgs g{};
-    g.A = X, g.lda = d_in, g.B = W, g.ldb = d_in, g.C = Y, g.ldc = d_out, g.bias = bias;
-    g.M = n, g.N = d_out, g.K = d_in, g.alpha = 1.0f, g.k_chunk = (d_in + 127) / 128 * 128;
-    g.a_bytes = n * d_in * 2, g.b_bytes = d_out * d_in * 2;
-    if (large_tiles_pay(g.M, g.N)) return launch_large<A_KCONTIG, B_KCONTIG>(g, stream);
-    if (RMM_TUNE_TINY_FIRST && tiny_tiles_pay(g.M, g.N)) return launch<RMM_TUNE_TINY, A_KCONTIG, B_KCONTIG, OUT_BF16>(g, 1, stream);
-    if (split_waves_pay(g.M, g.N, g.K)) return launch<RMM_TUNE_SPLIT, A_KCONTIG, B_KCONTIG, OUT_BF16>(g, 1, stream);
-    if (tiny_tiles_pay(g.M, g.N)) return launch<RMM_TUNE_TINY, A_KCONTIG, B_KCONTIG, OUT_BF16>(g, 1, stream);
-    return launch<RMM_TUNE_NT, A_KCONTIG, B_KCONTIG, OUT_BF16>(g, 1, stream);
+    const GemmArgs g = args_nt(X, W, bias, Y, n, d_in, d_out);
+    return launch_gemm<A_KCONTIG, B_KCONTIG, OUT_BF16>(gemm_cfg(g.M, g.N, g.K), g, stream);
 }
 
 hipError_t launch_linear_nn_bf16(const bf16_t *dY, const bf16_t *W, bf16_t *dX, int64_t n, int64_t d_in,
                                  int64_t d_out, hipStream_t stream) {
-    GemmArgs g{};
-    g.A = dY, g.lda = d_out, g.B = W, g.ldb = d_in, g.C = dX, g.ldc = d_in, g.bias = nullptr;
-    g.M = n, g.N = d_in, g.K = d_out, g.alpha = 1.0f, g.k_chunk = (d_out + 127) / 128 * 128;
-    g.a_bytes = n * d_out * 2, g.b_bytes = d_out * d_in * 2;
-    if (large_tiles_pay(g.M, g.N)) return launch_large<A_KCONTIG, B_NCONTIG>(g, stream);
-    if (RMM_TUNE_TINY_FIRST && tiny_tiles_pay(g.M, g.N)) return launch<RMM_TUNE_TINY, A_KCONTIG, B_NCONTIG, OUT_BF16>(g, 1, stream);
-    if (split_waves_pay(g.M, g.N, g.K)) return launch<RMM_TUNE_SPLIT, A_KCONTIG, B_NCONTIG, OUT_BF16>(g, 1, stream);
-    if (tiny_tiles_pay(g.M, g.N)) return launch<RMM_TUNE_TINY, A_KCONTIG, B_NCONTIG, OUT_BF16>(g, 1, stream);
-    return launch<RMM_TUNE_NN, A_KCONTIG, B_NCONTIG, OUT_BF16>(g, 1, stream);
+    const GemmArgs g = args_nn(dY, W, dX, n, d_in, d_out);
+    return launch_gemm<A_KCONTIG, B_NCONTIG, OUT_BF16>(gemm_cfg(g.M, g.N, g.K), g, stream);
 }
 
 hipError_t launch_dw_bf16(const bf16_t *G, const bf16_t *X_proj, bf16_t *dW, int64_t k, int64_t d_in, int64_t d_out,
@@ -1021,25 +220,20 @@ hipError_t launch_dw_bf16(const bf16_t *G, const bf16_t *X_proj, bf16_t *dW, int
     g.A = G, g.lda = d_out, g.B = X_proj, g.ldb = d_in, g.C = dW, g.ldc = d_in, g.bias = nullptr;
     g.M = d_out, g.N = d_in, g.K = k, g.alpha = 1.0f, g.k_chunk = (k + 127) / 128 * 128;
     g.a_bytes = k * d_out * 2, g.b_bytes = k * d_in * 2;
-    if (large_tiles_pay(g.M, g.N)) return launch_large<A_MCONTIG, B_NCONTIG>(g, stream);
-    if (RMM_TUNE_TINY_FIRST && tiny_tiles_pay(g.M, g.N)) return launch<RMM_TUNE_TINY, A_MCONTIG, B_NCONTIG, OUT_BF16>(g, 1, stream);
-    if (split_waves_pay(g.M, g.N, g.K)) return launch<RMM_TUNE_SPLIT, A_MCONTIG, B_NCONTIG, OUT_BF16>(g, 1, stream);
-    if (tiny_tiles_pay(g.M, g.N)) return launch<RMM_TUNE_TINY, A_MCONTIG, B_NCONTIG, OUT_BF16>(g, 1, stream);
-    return launch<RMM_TUNE_DW, A_MCONTIG, B_NCONTIG, OUT_BF16>(g, 1, stream);
+    return launch_gemm<A_MCONTIG, B_NCONTIG, OUT_BF16>(gemm_cfg(g.M, g.N, g.K), g, stream);
 }
 
-// Token slices of the sketch product: at most one (tile, slice) pair per compute unit where
-// the tile count allows, each slice a multiple of 128 tokens, none empty.
 // |X^T dY|_F^2 per tile for the variance monitors: the dW-type product (both operands stored
-// [token][feature]) with the squared-norm epilogue; same tile menu as the other products.
+// [token][feature]) with the squared-norm epilogue; the tile menu of the other products without
+// its 64 x 64 entry.
 static int xty_cfg(int64_t m, int64_t n, int64_t kk) {
-    return large_tiles_pay(m, n) ? 0 : split_waves_pay(m, n, kk) ? 1 : 2;
+    const int cfg = gemm_cfg(m, n, kk);
+    return cfg == GEMM_TINY ? (kk >= 1536 ? GEMM_SPLIT : GEMM_MID) : cfg;
 }
 
 int xty_sumsq_tiles(int64_t n, int64_t d_in, int64_t d_out) {
-    const bool large = xty_cfg(d_in, d_out, n) == 0;
-    const int64_t tm = large ? RMM_TUNE_LARGE_BM : 128, tn = large ? RMM_TUNE_LARGE_BN : 128;
-    return (int)(((d_in + tm - 1) / tm) * ((d_out + tn - 1) / tn));
+    const bool large = xty_cfg(d_in, d_out, n) == GEMM_LARGE;
+    return (int)tiles_of(d_in, d_out, large ? ShapeLarge::BM : 128, large ? ShapeLarge::BN : 128);
 }
 
 hipError_t launch_xty_sumsq_bf16(const bf16_t *X, const bf16_t *dY, double *part, int64_t n, int64_t d_in,
@@ -1048,144 +242,80 @@ hipError_t launch_xty_sumsq_bf16(const bf16_t *X, const bf16_t *dY, double *part
     g.A = X, g.lda = d_in, g.B = dY, g.ldb = d_out, g.C = part, g.ldc = d_out, g.bias = nullptr;
     g.M = d_in, g.N = d_out, g.K = n, g.alpha = 1.0f, g.k_chunk = (n + 127) / 128 * 128;
     g.a_bytes = n * d_in * 2, g.b_bytes = n * d_out * 2;
-    switch (xty_cfg(g.M, g.N, g.K)) {
-        case 0: return launch_large<A_MCONTIG, B_NCONTIG, OUT_SUMSQ>(g, stream);
-        case 1: return launch<RMM_TUNE_SPLIT, A_MCONTIG, B_NCONTIG, OUT_SUMSQ>(g, 1, stream);
-        default: return launch<RMM_TUNE_DW, A_MCONTIG, B_NCONTIG, OUT_SUMSQ>(g, 1, stream);
-    }
-}
-
-// Which sketch product kernel serves k > 64: LDS-generated 128x512 tiles for wide operands,
-// 64-row variants of it when k is small enough that padding k to 128 rows would waste much
-// (k = 410: 448 rows instead of 512) -- 64x512, or 64x384 where that divides d (768) --, else the
-// register-generated 128x256 kernel.
-enum { SK_NARROW = 0, SK_WIDE = 1, SK_WIDE64 = 2, SK_MID64 = 3, SK_MID = 4 };
-static int sketch_cfg(int64_t d, int64_t k) {
-    const bool rows64 = k <= RMM_TUNE_SK_ROWS64_MAX_K;
-    if (d >= RMM_TUNE_SK_WIDE_MIN_D) return rows64 ? SK_WIDE64 : SK_WIDE;
-    if (d % 384 == 0) return rows64 ? SK_MID64 : SK_MID;
-    return SK_NARROW;
-}
-
-static int sketch_slices(int64_t n, int64_t d, int64_t k, int64_t *k_chunk) {
-    const int cfg = sketch_cfg(d, k);
-    const int64_t bm = cfg == SK_NARROW ? RMM_TUNE_SK_BM : cfg == SK_WIDE ? RMM_TUNE_SKW_BM : cfg == SK_MID ? 128 : 64;
-    const int64_t bn = cfg == SK_NARROW ? RMM_TUNE_SK_BN : (cfg == SK_MID64 || cfg == SK_MID) ? 384 : RMM_TUNE_SKW_BN;
-    const int64_t tiles = ((k + bm - 1) / bm) * ((d + bn - 1) / bn);
-    const int64_t blocks = (n + 127) / 128;
-    int64_t s = RMM_TUNE_SK_WGS / tiles;
-    if (s > blocks) s = blocks;
-    if (s > 64) s = 64;
-    if (s < 1) s = 1;
-    *k_chunk = (blocks + s - 1) / s * 128;
-    return (int)((n + *k_chunk - 1) / *k_chunk);
-}
-
-template <int OUT>
-static hipError_t launch_sketch_cfg(int cfg, int kind, const GemmArgs &g, int splits, hipStream_t stream) {
-    switch (cfg) {
-        case SK_WIDE:
-            return kind == 0 ? launch<RMM_TUNE_SKW, A_GAUSS_LDS, B_NCONTIG, OUT>(g, splits, stream)
-                             : launch<RMM_TUNE_SKW, A_RADEM_LDS, B_NCONTIG, OUT>(g, splits, stream);
-        case SK_WIDE64:
-            return kind == 0 ? launch<64, RMM_TUNE_SKW_BN, 32, 2, 4, 1, A_GAUSS_LDS, B_NCONTIG, OUT>(g, splits, stream)
-                             : launch<64, RMM_TUNE_SKW_BN, 32, 2, 4, 1, A_RADEM_LDS, B_NCONTIG, OUT>(g, splits, stream);
-        case SK_MID64:
-            return kind == 0 ? launch<64, 384, 32, 2, 4, 1, A_GAUSS_LDS, B_NCONTIG, OUT>(g, splits, stream)
-                             : launch<64, 384, 32, 2, 4, 1, A_RADEM_LDS, B_NCONTIG, OUT>(g, splits, stream);
-        case SK_MID:
-            return kind == 0 ? launch<128, 384, 32, 2, 4, 1, A_GAUSS_LDS, B_NCONTIG, OUT>(g, splits, stream)
-                             : launch<128, 384, 32, 2, 4, 1, A_RADEM_LDS, B_NCONTIG, OUT>(g, splits, stream);
-        default:
-            return kind == 0 ? launch<RMM_TUNE_SK, A_GAUSS, B_NCONTIG, OUT>(g, splits, stream)
-                             : launch<RMM_TUNE_SK, A_RADEM, B_NCONTIG, OUT>(g, splits, stream);
-    }
-}
-
-// Same for the streaming kernel of small sketch sizes (256-column work-groups, one per compute unit).
-constexpr int64_t kSmallK = 64;
-static int smallk_slices(int64_t n, int64_t d, int64_t *k_chunk) {
-    const int64_t col_tiles = (d + 255) / 256, blocks = (n + 127) / 128;
-    int64_t s = RMM_TUNE_SMALLK_WGS / col_tiles;
-    if (s > blocks) s = blocks;
-    if (s < 1) s = 1;
-    *k_chunk = (blocks + s - 1) / s * 128;
-    return (int)((n + *k_chunk - 1) / *k_chunk);
+    return launch_gemm<A_MCONTIG, B_NCONTIG, OUT_SUMSQ>(xty_cfg(g.M, g.N, g.K), g, stream);
 }
 
 size_t sketch_workspace_bf16(int64_t n, int64_t d, int64_t k) {
     int64_t k_chunk;
-    const int s = k <= kSmallK ? smallk_slices(n, d, &k_chunk) : sketch_slices(n, d, k, &k_chunk);
+    const int s = k <= kSmallK ? smallk_slices(n, d, &k_chunk) : plan_sketch(n, d, k).splits;
     return s > 1 ? (size_t)s * (size_t)k * (size_t)d * sizeof(float) : 0;
 }
 
-template <int TM, int KIND>
-static hipError_t launch_smallk(const SmallkArgs &g, int slices, hipStream_t stream) {
-    constexpr int D = TM == 1 ? RMM_TUNE_SMALLK_D1 : RMM_TUNE_SMALLK_D2;
-    dim3 grid((unsigned)((g.d + 255) / 256), (unsigned)slices);
-    if (slices == 1)
-        sketch_smallk_kernel<TM, KIND, D, OUT_BF16><<<grid, 256, 0, stream>>>(g);
-    else
-        sketch_smallk_kernel<TM, KIND, D, OUT_F32_PARTIAL><<<grid, 256, 0, stream>>>(g);
-    return hipGetLastError();
-}
-
-namespace {
-// Brackets the product kernel (not the sum over token slices) with the caller's events.
-struct ProductEvents {
-    hipEvent_t begin, end;
-    hipStream_t stream;
-    ProductEvents(hipEvent_t b, hipEvent_t e, hipStream_t s) : begin(b), end(e), stream(s) {
-        if (begin != nullptr && end != nullptr) (void)hipEventRecord(begin, stream);
-    }
-    void done() {
-        if (begin != nullptr && end != nullptr) (void)hipEventRecord(end, stream);
-        begin = end = nullptr;
-    }
-    ~ProductEvents() { done(); }
-};
-}  // namespace
-
 hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d, int64_t k, int kind, SketchState st,
                               void *ws, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end) {
-    const float alpha = 1.0f / sqrtf((float)k);
-    ProductEvents pev(ev_begin, ev_end, stream);
+    EventPair pev(ev_begin, ev_end, stream);
     if (k <= kSmallK) {  // bound by one pass over A: streaming kernel
         SmallkArgs a{};
         a.A = A, a.n = n, a.d = d, a.k = k, a.a_bytes = n * d * 2, a.st = st;
-#ifdef RMM_DEBUG_TRACE
-        a.trace = g_trace;
-#endif
         const int slices = smallk_slices(n, d, &a.k_chunk);
-        a.C = slices == 1 ? (void *)out : ws, a.alpha = alpha;
+        a.C = slices == 1 ? (void *)out : ws, a.alpha = 1.0f / sqrtf((float)k);
         hipError_t e = k <= 32 ? (kind == 0 ? launch_smallk<1, 0>(a, slices, stream) : launch_smallk<1, 1>(a, slices, stream))
                                : (kind == 0 ? launch_smallk<2, 0>(a, slices, stream) : launch_smallk<2, 1>(a, slices, stream));
         pev.done();
         if (e != hipSuccess || slices == 1) return e;
-        const int64_t elems = k * d;
-        reduce_partials_kernel<<<(unsigned)((elems / 4 + 255) / 256), 256, 0, stream>>>((const float *)ws, out, elems,
-                                                                                         slices, k * d, alpha);
-        return hipGetLastError();
+        return launch_reduce(ws, out, k, d, slices, stream);
     }
-    GemmArgs g{};
-    g.A = nullptr, g.lda = 0, g.B = A, g.ldb = d, g.bias = nullptr;
-    g.M = k, g.N = d, g.K = n, g.st = st, g.ldc = d;
-    g.a_bytes = 0, g.b_bytes = n * d * 2;
-    const int splits = sketch_slices(n, d, k, &g.k_chunk);
-    const int cfg = sketch_cfg(d, k);
-    hipError_t e;
-    if (splits == 1) {
-        g.C = out, g.alpha = alpha;
-        return launch_sketch_cfg<OUT_BF16>(cfg, kind, g, 1, stream);
-    }
-    g.C = ws, g.alpha = 1.0f, g.split_stride = k * d;
-    e = launch_sketch_cfg<OUT_F32_PARTIAL>(cfg, kind, g, splits, stream);
+    const SketchPlan p = plan_sketch(n, d, k);
+    const GemmArgs g = args_sketch(A, n, d, k, st, p, out, ws);
+    if (p.splits == 1) return launch_sketch_cfg<OUT_BF16>(p.cfg, kind, g, 1, stream);
+    hipError_t e = launch_sketch_cfg<OUT_F32_PARTIAL>(p.cfg, kind, g, p.splits, stream);
     pev.done();
     if (e != hipSuccess) return e;
-    const int64_t elems = k * d;  // d % 8 == 0, so elems % 4 == 0
-    reduce_partials_kernel<<<(unsigned)((elems / 4 + 255) / 256), 256, 0, stream>>>((const float *)ws, out, elems,
-                                                                                     splits, k * d, alpha);
-    return hipGetLastError();
+    return launch_reduce(ws, out, k, d, p.splits, stream);
+}
+
+bool forward_pair_available(int64_t n, int64_t d_in, int64_t d_out, int64_t k) {
+    if (k <= kSmallK) return false;
+    return pair_ok(gemm_cfg(n, d_out, d_in), 3, plan_sketch(n, d_in, k), false);
+}
+
+hipError_t launch_forward_pair_bf16(const bf16_t *X, const bf16_t *W, const bf16_t *bias, bf16_t *Y, bf16_t *X_proj,
+                                    int64_t n, int64_t d_in, int64_t d_out, int64_t k, int kind, SketchState st, void *ws,
+                                    hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end) {
+    const GemmArgs ga = args_nt(X, W, bias, Y, n, d_in, d_out);
+    const SketchPlan p = plan_sketch(n, d_in, k);
+    const GemmArgs gb = args_sketch(X, n, d_in, k, st, p, X_proj, ws);
+    EventPair pev(ev_begin, ev_end, stream);
+    const int blocks_a = (int)tiles_of(ga.M, ga.N, ShapeLarge::BM, ShapeLarge::BN);
+    hipError_t e = launch_pair_nt(p.cfg, kind, ga, gb, blocks_a, (int)p.tiles, p.splits, stream);
+    pev.done();
+    if (e != hipSuccess) return e;
+    return launch_reduce(ws, X_proj, k, d_in, p.splits, stream);
+}
+
+bool backward_pair_available(int64_t n, int64_t d_in, int64_t d_out, int64_t k) {
+    if (k <= kSmallK) return false;
+    const int cfg = gemm_cfg(n, d_in, d_out);
+    return pair_ok(cfg, cfg == GEMM_SPLIT ? plain_depth(d_out, ShapeSplit::BK) : 3, plan_sketch(n, d_out, k), true);
+}
+
+hipError_t launch_backward_pair_bf16(const bf16_t *dY, const bf16_t *W, bf16_t *dX, bf16_t *G, int64_t n, int64_t d_in,
+                                     int64_t d_out, int64_t k, int kind, SketchState st, void *ws, hipStream_t stream,
+                                     hipEvent_t ev_begin, hipEvent_t ev_end) {
+    const GemmArgs ga = args_nn(dY, W, dX, n, d_in, d_out);
+    const SketchPlan p = plan_sketch(n, d_out, k);
+    const GemmArgs gb = args_sketch(dY, n, d_out, k, st, p, G, ws);
+    EventPair pev(ev_begin, ev_end, stream);
+    hipError_t e;
+    if (gemm_cfg(ga.M, ga.N, ga.K) == GEMM_LARGE)
+        e = launch_pair_nn_large(p.cfg, kind, ga, gb, (int)tiles_of(ga.M, ga.N, ShapeLarge::BM, ShapeLarge::BN), (int)p.tiles,
+                                 p.splits, stream);
+    else
+        e = launch_pair_nn_split(p.cfg, kind, ga, gb, (int)tiles_of(ga.M, ga.N, ShapeSplit::BM, ShapeSplit::BN), (int)p.tiles,
+                                 p.splits, stream);
+    pev.done();
+    if (e != hipSuccess) return e;
+    return launch_reduce(ws, G, k, d_out, p.splits, stream);
 }
 
 }  // namespace rmm
