@@ -61,7 +61,6 @@ GemmArgs args_nt(const bf16_t *X, const bf16_t *W, const bf16_t *bias, bf16_t *Y
     GemmArgs g{};
     g.A = X, g.lda = d_in, g.B = W, g.ldb = d_in, g.C = Y, g.ldc = d_out, g.bias = bias;
     g.M = n, g.N = d_out, g.K = d_in, g.alpha = 1.0f, g.k_chunk = (d_in + 127) / 128 * 128;
-    g.a_bytes = n * d_in * 2, g.b_bytes = d_out * d_in * 2;
     return g;
 }
 
@@ -69,7 +68,6 @@ GemmArgs args_nn(const bf16_t *dY, const bf16_t *W, bf16_t *dX, int64_t n, int64
     GemmArgs g{};
     g.A = dY, g.lda = d_out, g.B = W, g.ldb = d_in, g.C = dX, g.ldc = d_in, g.bias = nullptr;
     g.M = n, g.N = d_in, g.K = d_out, g.alpha = 1.0f, g.k_chunk = (d_out + 127) / 128 * 128;
-    g.a_bytes = n * d_out * 2, g.b_bytes = d_out * d_in * 2;
     return g;
 }
 
@@ -110,7 +108,6 @@ GemmArgs args_sketch(const bf16_t *A, int64_t n, int64_t d, int64_t k, SketchSta
     GemmArgs g{};
     g.A = nullptr, g.lda = 0, g.B = A, g.ldb = d, g.bias = nullptr;
     g.M = k, g.N = d, g.K = n, g.st = st, g.ldc = d, g.k_chunk = p.k_chunk;
-    g.a_bytes = 0, g.b_bytes = n * d * 2;
     if (p.splits == 1) {
         g.C = out, g.alpha = 1.0f / sqrtf((float)k);
     } else {
@@ -195,10 +192,12 @@ bool pair_ok(int cfg_a, int depth_a, const SketchPlan &p, bool nn) {
 }  // namespace
 
 bool mfma_shape_ok(int64_t n, int64_t d_in, int64_t d_out, int64_t k) {
-    // 16-byte chunks need widths that are multiples of 8; buffer loads need operands below 2^31 bytes.
-    const int64_t lim = ((int64_t)1 << 31) / 2;
-    const int64_t rows = n > k ? n : k, cols = d_in > d_out ? d_in : d_out;
-    return d_in % 8 == 0 && d_out % 8 == 0 && rows * cols < lim && d_in * d_out < lim;
+    // 16-byte chunks need widths that are multiples of 8; a buffer descriptor spans up to 256 rows
+    // of an operand with 32-bit byte offsets, so a row has to stay below 2^22 elements.  The token
+    // count and the sketch size are not limited here (operands of 2 GiB and more are fine).
+    (void)n, (void)k;
+    const int64_t lim = (int64_t)1 << 22;
+    return d_in % 8 == 0 && d_out % 8 == 0 && d_in < lim && d_out < lim;
 }
 
 hipError_t launch_linear_nt_bf16(const bf16_t *X, const bf16_t *W, const bf16_t *bias, bf16_t *Y, int64_t n,
@@ -219,7 +218,6 @@ hipError_t launch_dw_bf16(const bf16_t *G, const bf16_t *X_proj, bf16_t *dW, int
     g.accumulate = accumulate ? 1 : 0;
     g.A = G, g.lda = d_out, g.B = X_proj, g.ldb = d_in, g.C = dW, g.ldc = d_in, g.bias = nullptr;
     g.M = d_out, g.N = d_in, g.K = k, g.alpha = 1.0f, g.k_chunk = (k + 127) / 128 * 128;
-    g.a_bytes = k * d_out * 2, g.b_bytes = k * d_in * 2;
     return launch_gemm<A_MCONTIG, B_NCONTIG, OUT_BF16>(gemm_cfg(g.M, g.N, g.K), g, stream);
 }
 
@@ -241,7 +239,6 @@ hipError_t launch_xty_sumsq_bf16(const bf16_t *X, const bf16_t *dY, double *part
     GemmArgs g{};
     g.A = X, g.lda = d_in, g.B = dY, g.ldb = d_out, g.C = part, g.ldc = d_out, g.bias = nullptr;
     g.M = d_in, g.N = d_out, g.K = n, g.alpha = 1.0f, g.k_chunk = (n + 127) / 128 * 128;
-    g.a_bytes = n * d_in * 2, g.b_bytes = n * d_out * 2;
     return launch_gemm<A_MCONTIG, B_NCONTIG, OUT_SUMSQ>(xty_cfg(g.M, g.N, g.K), g, stream);
 }
 
@@ -256,7 +253,7 @@ hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d
     EventPair pev(ev_begin, ev_end, stream);
     if (k <= kSmallK) {  // bound by one pass over A: streaming kernel
         SmallkArgs a{};
-        a.A = A, a.n = n, a.d = d, a.k = k, a.a_bytes = n * d * 2, a.st = st;
+        a.A = A, a.n = n, a.d = d, a.k = k, a.st = st;
         const int slices = smallk_slices(n, d, &a.k_chunk);
         a.C = slices == 1 ? (void *)out : ws, a.alpha = 1.0f / sqrtf((float)k);
         hipError_t e = k <= 32 ? (kind == 0 ? launch_smallk<1, 0>(a, slices, stream) : launch_smallk<1, 1>(a, slices, stream))

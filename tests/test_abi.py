@@ -143,10 +143,13 @@ def test_new_entry_points_validate_before_launching(lib):
     assert lib.rmm_sketch_static(16384, 4096, 1638, 1, 0, st, fake, fake, None) == -5
 
 
-def test_operands_of_two_gib_or_more_leave_the_mfma_path(lib):
-    """The MFMA kernels address operands with 32-bit buffer offsets; a bf16 operand of 2^31 bytes
-    or more is served by the plain kernels, which need no partial-sum workspace."""
+def test_operands_of_two_gib_or_more_stay_on_the_mfma_path(lib):
+    """The MFMA kernels address an operand with 32-bit offsets from the rows a work-group reads,
+    so the operand's total size does not matter; what takes the plain kernels (no partial-sum
+    workspace) is a width that is not a multiple of 8 or a row of 2^22 elements or more."""
     bf16 = torch.bfloat16
     below = rmm.rmm_workspace_bytes((1 << 20) - 128, 1016, 8, 70, bf16, 0, binding.OP_FORWARD)     # 2.13e9 bytes < 2^31
     above = rmm.rmm_workspace_bytes((1 << 20) + 128, 1024, 8, 70, bf16, 0, binding.OP_FORWARD)     # 2^31 + ...
-    assert below > 0 and above == 0
+    assert below > 0 and above > 0
+    assert rmm.rmm_workspace_bytes(4096, 1 << 22, 8, 70, bf16, 0, binding.OP_FORWARD) == 0
+    assert rmm.rmm_workspace_bytes(4096, 1020, 8, 70, bf16, 0, binding.OP_FORWARD) == 0

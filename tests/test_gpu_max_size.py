@@ -1,6 +1,7 @@
-"""GPU: an operand beyond the 32-bit buffer range of the MFMA kernels (X of 2^31 + 2^18 bytes)
-goes through the plain kernels and still matches the oracle: Y and dX on sampled rows (they are
-row-wise independent), X_proj and dW in full, with the oracle's S applied to X in row blocks."""
+"""GPU: an operand of more than 2^31 bytes (X of 2^31 + 2^18 bytes) stays on the MFMA kernels, whose
+32-bit buffer offsets are relative to the rows a work-group reads, and matches the oracle: Y and dX
+on sampled rows (they are row-wise independent), X_proj and dW in full, with the oracle's S applied
+to X in row blocks.  k = 8 takes the streaming sketch kernel, k = 72 the tiled one."""
 import numpy as np
 import pytest
 import torch
@@ -13,8 +14,9 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
 
-def test_operand_beyond_two_gib():
-    n, d_in, d_out, k = (1 << 20) + 128, 1024, 8, 8
+@pytest.mark.parametrize("k", [8, 72])
+def test_operand_beyond_two_gib(k):
+    n, d_in, d_out = (1 << 20) + 128, 1024, 8
     kind, seed, offset = rmm.RADEMACHER, 77, 3
     assert n * d_in * 2 >= 1 << 31
     block = 1 << 16
@@ -25,7 +27,7 @@ def test_operand_beyond_two_gib():
     W64 = synth.pattern_rows(0, d_out, d_in, 29, 13) / 16.0
     dY64 = synth.pattern_rows(0, n, d_out, 53, 11)
     W, dY = (torch.from_numpy(a).to(torch.bfloat16).to(DEV) for a in (W64, dY64))
-    assert rmm.rmm_workspace_bytes(n, d_in, d_out, k, torch.bfloat16, kind, 0) == 0      # not the MFMA path
+    assert rmm.rmm_workspace_bytes(n, d_in, d_out, k, torch.bfloat16, kind, 0) > 0       # token slices: the MFMA path
     Y, Xp = rmm.rmm_forward(X, W, None, k, kind, seed, offset)
     dX, dW, _ = rmm.rmm_backward(dY, W, Xp, kind, seed, offset)
     torch.cuda.synchronize()
