@@ -25,12 +25,19 @@ PEAK_HBM_GBS = 8000.0
 
 STAGES = ["fwd_Y", "fwd_Xproj", "bwd_dX", "bwd_G", "bwd_dW"]
 STAGE_ID = {"fwd_Y": 0, "fwd_Xproj": 1, "bwd_dX": 2, "bwd_G": 3, "bwd_dW": 4}
-# One kernel per stage carries its flops; for the two sketch stages that is the
-# product kernel, timed without the small kernel that sums the token-slice partials.
+# One kernel per stage carries its flops; for the two sketch stages that is the product kernel,
+# timed without the small kernel that sums the token-slice partials.
 KERNEL_STAGE_ID = {"fwd_Y": 0, "fwd_Xproj": 6, "bwd_dX": 2, "bwd_G": 7, "bwd_dW": 4}
+# Where the library issues Y with the sketch of X (dX with the sketch of dY) as ONE launch, that
+# paired kernel is what a step really runs; the per-product stages above are then timed on the
+# separate-launch path (same kernels, one after the other).
+PAIR_STAGE_ID = {"fwd_pair": 8, "bwd_pair": 9}
+PAIR_PARTS = {"fwd_pair": ("fwd_Y", "fwd_Xproj"), "bwd_pair": ("bwd_dX", "bwd_G")}
 KERNEL_NAME = {"fwd_Y": "gemm_mfma_kernel (X, W^T operands)", "fwd_Xproj": "sketch product kernel on X",
                "bwd_dX": "gemm_mfma_kernel (dY, W operands)", "bwd_G": "sketch product kernel on dY",
-               "bwd_dW": "gemm_mfma_kernel (G^T, X_proj operands)"}
+               "bwd_dW": "gemm_mfma_kernel (G^T, X_proj operands)",
+               "fwd_pair": "gemm_pair_kernel (Y = X W^T with the sketch product of X, one launch)",
+               "bwd_pair": "gemm_pair_kernel (dX = dY W with the sketch product of dY, one launch)"}
 
 
 def stage_flops(n, d_in, d_out, k):
@@ -45,17 +52,31 @@ def stage_bytes(n, d_in, d_out, k, e):
             "bwd_dW": e * (k * d_out + k * d_in + d_in * d_out)}
 
 
-def read_traffic(workload, stage):
-    """HBM bytes per launch of `stage` from the committed counter summary, if any
-    (line `traffic_bytes_per_launch <workload> <stage> <bytes>` in profiles/hbm_traffic.txt)."""
+def with_pairs(per_stage, shared):
+    """Adds the paired kernels to a per-stage dict: the sum of their two products, less what the
+    pair shares (the one read of X, of dY)."""
+    out = dict(per_stage)
+    for pair, (a, b) in PAIR_PARTS.items():
+        out[pair] = per_stage[a] + per_stage[b] - shared.get(pair, 0)
+    return out
+
+
+def read_traffic(workload, stage, kernels_version):
+    """HBM bytes per launch of `stage` from the committed counter summary (line
+    `traffic_bytes_per_launch <workload> <stage> <bytes>` in profiles/hbm_traffic.txt), or None when
+    there is none or when it was measured on another version of the kernels (line
+    `kernels_version <rmm_version()>`): a stale figure is worse than none."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     if not os.path.exists(path):
         return None
+    found, version = None, None
     for line in open(path):
         t = line.split()
+        if len(t) == 2 and t[0] == "kernels_version":
+            version = int(t[1])
         if len(t) == 4 and t[0] == "traffic_bytes_per_launch" and t[1] == workload and t[2] == stage:
-            return float(t[3])
-    return None
+            found = float(t[3])
+    return found if version == kernels_version else None
 
 
 def cpu_baseline(cfg, kind, budget_s=10.0):
@@ -90,7 +111,7 @@ def cpu_baseline(cfg, kind, budget_s=10.0):
             "ms_per_step": dt / reps * 1e3}
 
 
-def sketch_roofline(torch, rmm, binding, dev, kind, kind_name, n=16384, d=4096, k=32, reps=30):
+def sketch_roofline(torch, rmm, binding, dev, kind, kind_name, version, n=16384, d=4096, k=32, reps=30):
     """rmm_sketch (S^T A) at small k on a RoBERTa-large sized operand: bound by one read of A.
     Three operands are rotated (402 MB) so that no call finds its input in the last-level cache.
     `achieved` is that of the streaming product kernel alone (events recorded by the library
@@ -124,7 +145,7 @@ def sketch_roofline(torch, rmm, binding, dev, kind, kind_name, n=16384, d=4096, 
     return {"workload": "rmm_sketch N=%d d=%d k=%d (%s), bf16" % (n, d, k, kind_name), "bound": "hbm",
             "kernel": "sketch_smallk_kernel", "achieved": nbytes / (kms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
             "unit": "GB/s", "frac": nbytes / (kms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-            "traffic": read_traffic("sketch_n%d_d%d_k%d" % (n, d, k), "product"), "avg_launch_ms": kms,
+            "traffic": read_traffic("sketch_n%d_d%d_k%d" % (n, d, k), "product", version), "avg_launch_ms": kms,
             "avg_call_ms": cms, "algorithmic_bytes_per_launch": nbytes}
 
 
@@ -205,6 +226,130 @@ def bench_stack(args, torch, rmm, synth, dev, kind):
     return 0
 
 
+class LayerRun:
+    """One layer workload resident in HBM (rotating buffer sets) and the calls that make a step."""
+
+    def __init__(self, torch, rmm, binding, synth, dev, cfg, kind, nsets):
+        self.torch, self.rmm, self.kind, self.cfg = torch, rmm, kind, cfg
+        n, d_in, d_out, k = cfg["n"], cfg["d_in"], cfg["d_out"], cfg["k"]
+        tdtype = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
+        Xc, Wc, dYc = synth.layer_inputs(n, d_in, d_out, cfg["dtype"], cfg["seeds"])
+        self.sets = []
+        for _ in range(max(1, nsets)):
+            # every set holds the same values (so results are comparable) at its own addresses
+            self.sets.append(dict(X=Xc.to(dev).clone(), W=Wc.to(dev).clone(), dY=dYc.to(dev).clone(),
+                                  Y=torch.empty((n, d_out), dtype=tdtype, device=dev),
+                                  Xp=torch.empty((k, d_in), dtype=tdtype, device=dev),
+                                  dX=torch.empty((n, d_in), dtype=tdtype, device=dev),
+                                  dW=torch.empty((d_out, d_in), dtype=tdtype, device=dev)))
+        ws_bytes = max(rmm.rmm_workspace_bytes(n, d_in, d_out, k, tdtype, kind, binding.OP_FORWARD),
+                       rmm.rmm_workspace_bytes(n, d_in, d_out, k, tdtype, kind, binding.OP_BACKWARD), 16)
+        self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self.paired = {"fwd_pair": rmm.rmm_uses_paired_launch(n, d_in, d_out, k, tdtype, kind, binding.OP_FORWARD),
+                       "bwd_pair": rmm.rmm_uses_paired_launch(n, d_in, d_out, k, tdtype, kind, binding.OP_BACKWARD)}
+
+    def step(self, i, profile=None):
+        b, k, c = self.sets[i % len(self.sets)], self.cfg["k"], self.cfg
+        # each pass records the events only if the stage id is one of its own
+        self.rmm.rmm_forward(b["X"], b["W"], None, k, self.kind, c["seed"], i, Y=b["Y"], X_proj=b["Xp"], ws=self.ws,
+                             profile=profile)
+        self.rmm.rmm_backward(b["dY"], b["W"], b["Xp"], self.kind, c["seed"], i, dX=b["dX"], dW=b["dW"], ws=self.ws,
+                              profile=profile)
+
+    def new_events(self, count):
+        evs = []
+        for _ in range(count):
+            a, b = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
+            a.record()
+            b.record()          # recording once creates the handles the library re-records
+            evs.append((a, b))
+        self.torch.cuda.synchronize()
+        return evs
+
+    def median_ms(self, stage_id, reps):
+        evs = self.new_events(reps)
+        for r in range(reps):
+            self.step(r, (stage_id, evs[r][0], evs[r][1]))
+        self.torch.cuda.synchronize()
+        return sorted(a.elapsed_time(b) for a, b in evs)[reps // 2]
+
+    def stage_table(self, reps):
+        """(stage ms, ms of the kernel that carries the stage's flops, ms of the paired kernels in use)."""
+        stage_ms, kernel_ms, pair_ms = {}, {}, {}
+        for name in STAGES:
+            stage_ms[name] = self.median_ms(STAGE_ID[name], reps)
+            kernel_ms[name] = stage_ms[name] if KERNEL_STAGE_ID[name] == STAGE_ID[name] else \
+                self.median_ms(KERNEL_STAGE_ID[name], reps)
+        for name, sid in PAIR_STAGE_ID.items():
+            if self.paired[name]:
+                pair_ms[name] = self.median_ms(sid, reps)
+        return stage_ms, kernel_ms, pair_ms
+
+    def step_ms(self, steps):
+        for i in range(3):
+            self.step(i)
+        self.torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            self.step(i)
+        self.torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+
+
+def layer_report(run, cfg, kind_name, steps, peaks):
+    """Step time and per-kernel TFLOP/s (fraction of the published bf16 peak, and of the measured
+    MFMA ceiling when given) of one more workload, for the bench line's side objects."""
+    n, d_in, d_out, k = cfg["n"], cfg["d_in"], cfg["d_out"], cfg["k"]
+    ms = run.step_ms(steps)
+    stage_ms, kernel_ms, pair_ms = run.stage_table(reps=5)
+    fl = with_pairs(stage_flops(n, d_in, d_out, k), {})
+    kernels = {}
+    for name, t in list(kernel_ms.items()) + list(pair_ms.items()):
+        tf = fl[name] / (t * 1e-3) / 1e12
+        kernels[name] = {"ms": t, "tflops": tf, "frac": tf / PEAK_BF16_TFLOPS}
+        if peaks:
+            kernels[name]["frac_of_measured_mfma"] = tf / peaks["mfma_bf16_tflops"]
+    total = sum(stage_flops(n, d_in, d_out, k).values())
+    return {"workload": "N=%d tokens, d_in=%d, d_out=%d, k=%d (%s sketch), bf16" % (n, d_in, d_out, k, kind_name),
+            "ms_per_step": ms, "tflops": total / (ms * 1e-3) / 1e12, "steps": steps, "stages_ms": stage_ms,
+            "kernels": kernels}
+
+
+def measured_peaks(torch, rmm, dev, reps=5):
+    """What a kernel that only issues MFMAs, and one that only reads memory, reach on this machine
+    (rmm_probe_mfma on one work-group per compute unit; rmm_probe_read over three rotating 512 MiB
+    buffers, larger together than the last-level cache)."""
+    sink = torch.zeros(1024, dtype=torch.uint8, device=dev)
+    cus = torch.cuda.get_device_properties(dev).multi_processor_count
+
+    def timed(fn):
+        best = None
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            work = fn()
+            b.record()
+            torch.cuda.synchronize()
+            rate = work / (a.elapsed_time(b) * 1e-3)
+            best = rate if best is None or rate > best else best
+        return best
+
+    rmm.rmm_probe_mfma(cus, 200, sink)
+    mfma = timed(lambda: rmm.rmm_probe_mfma(cus, 20000, sink)) / 1e12
+    bufs = [torch.ones(512 << 20, dtype=torch.uint8, device=dev) for _ in range(3)]
+    turn = [0]
+
+    def read():
+        turn[0] += 1
+        return rmm.rmm_probe_read(bufs[turn[0] % 3], cus * 8, sink)
+
+    read()
+    hbm = timed(read) / 1e9
+    return {"mfma_bf16_tflops": mfma, "hbm_read_gbs": hbm, "compute_units": cus,
+            "how": "best of %d launches: 32x32x16 bf16 MFMAs from registers on one 4-wave work-group per compute unit; "
+                   "one streaming read of 512 MiB (three buffers in turn)" % reps}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -221,6 +366,10 @@ def main():
                     help="skip the small-k rmm_sketch measurement against the HBM roofline")
     ap.add_argument("--no-variance-monitor", action="store_true",
                     help="skip timing rmm_variance_stats on the workload's X and dY")
+    ap.add_argument("--no-measured-peaks", action="store_true",
+                    help="skip the pure-MFMA and streaming-read probes (fractions of measured ceilings)")
+    ap.add_argument("--no-extra-workloads", action="store_true",
+                    help="skip the RoBERTa-large FFN shape and the other sketch kind (side objects of the line)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="only run a plain copy of this many MiB (counter calibration) and exit")
     args = ap.parse_args()
@@ -254,80 +403,47 @@ def main():
         cfg["k"] = args.k
     kind = rmm.GAUSSIAN if args.kind == "gaussian" else rmm.RADEMACHER
     n, d_in, d_out, k = cfg["n"], cfg["d_in"], cfg["d_out"], cfg["k"]
-    tdtype = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
     esize = 2 if cfg["dtype"] == "bf16" else 4
+    version = rmm.rmm_version()
 
-    Xc, Wc, dYc = synth.layer_inputs(n, d_in, d_out, cfg["dtype"], cfg["seeds"])
-    sets = []
-    for s in range(max(1, args.sets)):
-        # every set holds the same values (so results are comparable) at its own addresses
-        sets.append(dict(X=Xc.to(dev).clone(), W=Wc.to(dev).clone(), dY=dYc.to(dev).clone(),
-                         Y=torch.empty((n, d_out), dtype=tdtype, device=dev),
-                         Xp=torch.empty((k, d_in), dtype=tdtype, device=dev),
-                         dX=torch.empty((n, d_in), dtype=tdtype, device=dev),
-                         dW=torch.empty((d_out, d_in), dtype=tdtype, device=dev)))
-    ws_bytes = max(rmm.rmm_workspace_bytes(n, d_in, d_out, k, tdtype, kind, binding.OP_FORWARD),
-                   rmm.rmm_workspace_bytes(n, d_in, d_out, k, tdtype, kind, binding.OP_BACKWARD), 16)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-    seed = cfg["seed"]
-
-    def step(i, profile=None):
-        b = sets[i % len(sets)]
-        # each pass records the events only if the stage id is one of its own
-        rmm.rmm_forward(b["X"], b["W"], None, k, kind, seed, i, Y=b["Y"], X_proj=b["Xp"], ws=ws, profile=profile)
-        rmm.rmm_backward(b["dY"], b["W"], b["Xp"], kind, seed, i, dX=b["dX"], dW=b["dW"], ws=ws, profile=profile)
-
-    def new_events(count):
-        evs = []
-        for _ in range(count):
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            b.record()          # recording once creates the handles the library re-records
-            evs.append((a, b))
-        torch.cuda.synchronize()
-        return evs
-
-    # ---- warm-up; the last warm-up steps also time every stage once to find the slowest
+    run = LayerRun(torch, rmm, binding, synth, dev, cfg, kind, args.sets)
     for i in range(args.warmup):
-        step(i)
+        run.step(i)
     torch.cuda.synchronize()
-    stage_ms, kernel_ms = {}, {}
-    reps = 5
+    # the last warm-up steps time every stage once (separate launches) and the paired kernels, to
+    # find the slowest kernel of the path a step really takes
+    stage_ms, kernel_ms, pair_ms = run.stage_table(reps=5)
+    real = dict(pair_ms)
+    for pair, parts in PAIR_PARTS.items():
+        if pair not in pair_ms:
+            for part in parts:
+                real[part] = kernel_ms[part]
+    real["bwd_dW"] = kernel_ms["bwd_dW"]
+    dominant = max(real, key=real.get)
+    dom_idx = PAIR_STAGE_ID.get(dominant, KERNEL_STAGE_ID.get(dominant))
 
-    def median_ms(stage_id):
-        evs = new_events(reps)
-        for r in range(reps):
-            step(r, (stage_id, evs[r][0], evs[r][1]))
-        torch.cuda.synchronize()
-        return sorted(a.elapsed_time(b) for a, b in evs)[reps // 2]
-
-    for name in STAGES:
-        stage_ms[name] = median_ms(STAGE_ID[name])
-        kernel_ms[name] = stage_ms[name] if KERNEL_STAGE_ID[name] == STAGE_ID[name] else median_ms(KERNEL_STAGE_ID[name])
-    dominant = max(kernel_ms, key=kernel_ms.get)
-    dom_idx = KERNEL_STAGE_ID[dominant]
-
-    # ---- timed region: exactly `steps` steps, events around the dominant stage of every step
-    evs = new_events(args.steps)
+    # ---- timed region: exactly `steps` steps, events around the dominant kernel of every step
+    evs = run.new_events(args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i, (dom_idx, evs[i][0], evs[i][1]))
+        run.step(i, (dom_idx, evs[i][0], evs[i][1]))
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     dom_ms = sum(a.elapsed_time(b) for a, b in evs) / args.steps
     # what an event pair with nothing between it measures on this stream (for comparing the
     # event-bracketed duration with the profiler's kernel duration; not subtracted anywhere)
-    cal = new_events(50)
+    cal = run.new_events(50)
     for a, b in cal:
         a.record()
         b.record()
     torch.cuda.synchronize()
     empty_pair_ms = sorted(a.elapsed_time(b) for a, b in cal)[len(cal) // 2]
 
-    fl = stage_flops(n, d_in, d_out, k)
-    by = stage_bytes(n, d_in, d_out, k, esize)
-    total_flops = sum(fl.values())
+    shared = {"fwd_pair": esize * n * d_in, "bwd_pair": esize * n * d_out}     # X / dY is read once by a pair
+    fl = with_pairs(stage_flops(n, d_in, d_out, k), {})
+    by = with_pairs(stage_bytes(n, d_in, d_out, k, esize), shared)
+    total_flops = sum(stage_flops(n, d_in, d_out, k).values())
     ms_per_step = dt / args.steps * 1e3
     value = total_flops / (ms_per_step * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if cfg["dtype"] == "bf16" else PEAK_F32_TFLOPS
@@ -341,23 +457,40 @@ def main():
         "config": {"workload": "%s: N=%d tokens, d_in=%d, d_out=%d, k=%d (%s sketch), %s, X,dY~N(0,1), "
                                "W~N(0,%s), %d rotating buffer sets"
                                % (args.workload, n, d_in, d_out, k, args.kind, cfg["dtype"],
-                                  "0.02^2" if cfg["dtype"] == "bf16" else "1/d_in", len(sets)),
+                                  "0.02^2" if cfg["dtype"] == "bf16" else "1/d_in", len(run.sets)),
                    "flops_per_step": total_flops,
                    "saved_activation_bytes": saved, "plain_layer_saved_bytes": n * d_in * esize,
-                   "saved_fraction": saved / (n * d_in * esize)},
+                   "saved_fraction": saved / (n * d_in * esize), "kernels_version": version},
         "roofline": {"bound": "mfma" if cfg["dtype"] == "bf16" else "alu",
-                     "kernel": KERNEL_NAME[dominant] if cfg["dtype"] == "bf16" else "gemm_plain_kernel (%s)" % dominant, "stage": dominant, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": read_traffic(args.workload, dominant),
+                     "kernel": KERNEL_NAME[dominant] if cfg["dtype"] == "bf16" else "gemm_plain_kernel (%s)" % dominant,
+                     "stage": dominant, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": read_traffic(args.workload, dominant, version),
                      "avg_launch_ms": dom_ms, "empty_event_pair_ms": empty_pair_ms,
                      "flops_per_launch": fl[dominant],
                      "algorithmic_bytes_per_launch": by[dominant]},
-        "stages_ms": stage_ms, "stage_kernel_ms": kernel_ms,
+        "stages_ms": stage_ms, "stage_kernel_ms": kernel_ms, "paired_kernel_ms": pair_ms,
         "stages_tflops": {s: fl[s] / (stage_ms[s] * 1e-3) / 1e12 for s in STAGES},
     }
+    bf16 = cfg["dtype"] == "bf16"
+    if not args.no_measured_peaks:
+        out["measured_peaks"] = mp = measured_peaks(torch, rmm, dev)
+        if bf16:
+            out["roofline"]["frac_of_measured_mfma"] = achieved / mp["mfma_bf16_tflops"]
+    if not args.no_extra_workloads and bf16:
+        # the shape the MFMA targets are quoted on, and the other sketch kind at the headline shape
+        big = dict(synth.CONFIGS["c4_large_ffn_up"])
+        out["large_shape"] = layer_report(LayerRun(torch, rmm, binding, synth, dev, big, kind, 2), big, args.kind, 20,
+                                          out.get("measured_peaks"))
+        other = rmm.RADEMACHER if kind == rmm.GAUSSIAN else rmm.GAUSSIAN
+        out["other_kind"] = layer_report(LayerRun(torch, rmm, binding, synth, dev, cfg, other, args.sets), cfg,
+                                         "rademacher" if other == rmm.RADEMACHER else "gaussian", 50,
+                                         out.get("measured_peaks"))
     if not args.no_sketch_roofline:
-        out["sketch_hbm_roofline"] = sketch_roofline(torch, rmm, binding, dev, kind, args.kind)
-    if not args.no_variance_monitor and cfg["dtype"] == "bf16":
-        out["variance_monitor"] = variance_monitor(torch, rmm, sets[0]["X"], sets[0]["dY"], k, kind)
+        out["sketch_hbm_roofline"] = sk = sketch_roofline(torch, rmm, binding, dev, kind, args.kind, version)
+        if "measured_peaks" in out:
+            sk["frac_of_measured_read"] = sk["achieved"] / out["measured_peaks"]["hbm_read_gbs"]
+    if not args.no_variance_monitor and bf16:
+        out["variance_monitor"] = variance_monitor(torch, rmm, run.sets[0]["X"], run.sets[0]["dY"], k, kind)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, kind)
     print(json.dumps(out))

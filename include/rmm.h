@@ -18,14 +18,21 @@
  *     undefined on entry and on return.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
  *     work is enqueued on it and the call returns without waiting.
- *   - Output buffers are overwritten, never accumulated into.
+ *   - Output buffers are overwritten; the one entry point that adds to what its
+ *     outputs hold is rmm_backward_accumulate.
  *   - Return value: RMM_OK or a negative rmm_status_t.  Nothing is printed, no
- *     exception crosses the boundary, the process is never aborted.  On an
- *     error return no kernel has been launched.
+ *     exception crosses the boundary, the process is never aborted.  Arguments,
+ *     sizes and the workspace are checked before anything is launched, so
+ *     RMM_ERR_INVALID_ARG, RMM_ERR_UNSUPPORTED, RMM_ERR_WORKSPACE and
+ *     RMM_ERR_SCRATCH_LIMIT mean that no kernel ran.  RMM_ERR_LAUNCH (the HIP
+ *     runtime refused a launch) can come after earlier kernels of the same call
+ *     were enqueued; the outputs are then undefined.
  *   - The library holds no mutable global state and calls are re-entrant; the one exception is
  *     rmm_sketch_static, whose scratch array is shared by all calls on a GPU (see there).
  *   - dtype RMM_DTYPE_BF16: inputs, Y, dX, X_proj, dW are bfloat16 (round to
- *     nearest even from fp32 accumulators); bias / dbias are bfloat16 too.
+ *     nearest even from fp32 accumulators); bias / dbias are bfloat16 too and,
+ *     like every other pointer, 16-byte aligned (a misaligned one is
+ *     RMM_ERR_INVALID_ARG).
  *     dtype RMM_DTYPE_F32: everything is fp32.
  *
  * The sketch.  state = (seed, offset).  Entry (i, j) of S (token i, sketch
@@ -116,7 +123,9 @@ int rmm_sketch_static(int64_t n, int64_t d, int64_t k, int dtype, int kind, rmm_
 /* Algorithm 1, Forward: Y[n x d_out] = X[n x d_in] W[d_out x d_in]^T (+ bias[d_out] on
  * every row if bias != NULL; Eq. 1), X_proj[k x d_in] = S^T X.  After the call the
  * caller may drop X and keeps X_proj and `state` for the backward call: the saved
- * bytes are k*d_in*sizeof(dtype) + 16 instead of n*d_in*sizeof(dtype) (Section 2.4.1). */
+ * bytes are k*d_in*sizeof(dtype) + 16 instead of n*d_in*sizeof(dtype) (Section 2.4.1).
+ * X_proj may be NULL when no backward pass will follow (inference): the sketch is then
+ * skipped, k and state are ignored beyond validation, and no workspace is needed. */
 int rmm_forward(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *X, const void *W,
                 const void *bias, void *Y, void *X_proj, void *ws, size_t ws_bytes, void *stream);
 
@@ -192,6 +201,22 @@ int rmm_backward_profiled(const rmm_layer_desc_t *desc, rmm_rng_state_t state, c
 int rmm_sketch_profiled(int64_t n, int64_t d, int64_t k, int dtype, int kind, rmm_rng_state_t state,
                         const void *A, void *A_proj, void *ws, size_t ws_bytes, void *stream,
                         void *ev_begin, void *ev_end);
+
+/* Whether an unprofiled rmm_forward (op = RMM_OP_FORWARD) / rmm_backward with dX (RMM_OP_BACKWARD)
+ * of this shape issues its two independent products as one paired launch (RMM_STAGE_FWD_PAIR /
+ * RMM_STAGE_BWD_PAIR): 1 or 0; 0 for an invalid descriptor. */
+int rmm_uses_paired_launch(const rmm_layer_desc_t *desc, int op);
+
+/* Ceilings of the chip as a kernel sees them, for reporting measured fractions beside the
+ * published peaks (the caller times the launch with events).
+ * rmm_probe_mfma: `work_groups` work-groups of four waves, each wave issuing 16 * iters
+ *   independent 32x32x16 bf16 MFMAs from registers: work_groups * 4 * 16 * iters * 32768 flop.
+ * rmm_probe_read: streams `bytes` bytes (rounded down to 16) from `src` (device, 16-byte aligned)
+ *   once with 16-byte loads, split evenly over `work_groups` work-groups.
+ * `sink` is a device buffer of at least 1 KiB that keeps the work alive; it is practically never
+ * written. */
+int rmm_probe_mfma(int work_groups, int iters, void *sink, void *stream);
+int rmm_probe_read(const void *src, size_t bytes, int work_groups, void *sink, void *stream);
 
 /* Test hooks for the bit-exactness requirement on the generator.
  *

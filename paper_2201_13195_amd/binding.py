@@ -69,6 +69,12 @@ def load_library():
     L.rmm_backward_accumulate.argtypes = L.rmm_backward.argtypes
     L.rmm_backward_profiled.restype = ci
     L.rmm_backward_profiled.argtypes = L.rmm_backward.argtypes + [ci, vp, vp]
+    L.rmm_uses_paired_launch.restype = ci
+    L.rmm_uses_paired_launch.argtypes = [ctypes.POINTER(_Desc), ci]
+    L.rmm_probe_mfma.restype = ci
+    L.rmm_probe_mfma.argtypes = [ci, ci, vp, vp]
+    L.rmm_probe_read.restype = ci
+    L.rmm_probe_read.argtypes = [vp, sz, ci, vp, vp]
     L.rmm_debug_philox.restype = ci
     L.rmm_debug_philox.argtypes = [_State, u32, u32, i64, vp, vp]
     L.rmm_debug_sketch_tile.restype = ci
@@ -186,22 +192,23 @@ def _event_args(profile):
     return int(stage), ctypes.c_void_p(begin.cuda_event), ctypes.c_void_p(end.cuda_event)
 
 
-def rmm_forward(X, W, bias, k, kind, seed, offset, Y=None, X_proj=None, ws=None, profile=None):
-    """Algorithm 1 forward.  Returns (Y, X_proj)."""
+def rmm_forward(X, W, bias, k, kind, seed, offset, Y=None, X_proj=None, ws=None, profile=None, need_xproj=True):
+    """Algorithm 1 forward.  Returns (Y, X_proj); with need_xproj=False (no backward pass will
+    follow) the sketch is skipped and X_proj is None."""
     n, d_in = X.shape
     d_out = W.shape[0]
     if Y is None:
         Y = torch.empty((n, d_out), dtype=X.dtype, device=X.device)
-    if X_proj is None:
+    if X_proj is None and need_xproj:
         X_proj = torch.empty((k, d_in), dtype=X.dtype, device=X.device)
     desc = _desc(n, d_in, d_out, k, X.dtype, kind)
-    need = rmm_workspace_bytes(n, d_in, d_out, k, X.dtype, kind, OP_FORWARD)
+    need = rmm_workspace_bytes(n, d_in, d_out, k, X.dtype, kind, OP_FORWARD) if need_xproj else 0
     ws, wsp, wsb = _workspace(ws, need, X.device)
     rc = load_library().rmm_forward_profiled(ctypes.byref(desc), _State(seed, offset), _ptr(X, "X"),
                                              _ptr(W, "W", X.dtype, (d_out, d_in)),
                                              _ptr(bias, "bias", X.dtype, (d_out,), optional=True),
                                              _ptr(Y, "Y", X.dtype, (n, d_out)),
-                                             _ptr(X_proj, "X_proj", X.dtype, (k, d_in)),
+                                             _ptr(X_proj, "X_proj", X.dtype, (k, d_in), optional=not need_xproj),
                                              wsp, wsb, _stream(X), *_event_args(profile))
     if rc != 0:
         raise RmmError(rc, "rmm_forward")
@@ -236,6 +243,27 @@ def rmm_backward(dY, W, X_proj, kind, seed, offset, need_dX=True, need_dbias=Fal
     if rc != 0:
         raise RmmError(rc, "rmm_backward")
     return dX, dW, dbias
+
+
+def rmm_uses_paired_launch(n, d_in, d_out, k, dtype, kind, op):
+    return bool(load_library().rmm_uses_paired_launch(ctypes.byref(_desc(n, d_in, d_out, k, dtype, kind)), int(op)))
+
+
+def rmm_probe_mfma(work_groups, iters, sink):
+    """Pure MFMA loop (work_groups x 4 waves x 16 x iters MFMAs of 32768 flop); returns the flop count."""
+    rc = load_library().rmm_probe_mfma(int(work_groups), int(iters), _ptr(sink, "sink"), _stream(sink))
+    if rc != 0:
+        raise RmmError(rc, "rmm_probe_mfma")
+    return work_groups * 4 * 16 * iters * 32768
+
+
+def rmm_probe_read(src, work_groups, sink):
+    """One streaming read of `src` (a contiguous GPU tensor); returns the byte count."""
+    nbytes = src.numel() * src.element_size() // 16 * 16
+    rc = load_library().rmm_probe_read(_ptr(src, "src"), nbytes, int(work_groups), _ptr(sink, "sink"), _stream(src))
+    if rc != 0:
+        raise RmmError(rc, "rmm_probe_read")
+    return nbytes
 
 
 def rmm_debug_philox(seed, offset, c0, c1, ncalls, device="cuda"):

@@ -131,7 +131,7 @@ template <typename T>
 int forward_impl(const rmm_layer_desc_t *d, SketchState st, const void *X, const void *W, const void *bias, void *Y,
                  void *X_proj, void *ws, hipStream_t stream, const StageEvents &ev) {
     const bool mfma = use_mfma(d);
-    if (mfma && !separate_stage(ev.stage) && forward_pair_available(d->n, d->d_in, d->d_out, d->k)) {
+    if (X_proj != nullptr && mfma && !separate_stage(ev.stage) && forward_pair_available(d->n, d->d_in, d->d_out, d->k)) {
         const bool timed = ev.stage == RMM_STAGE_FWD_PAIR;
         return from_hip(launch_forward_pair_bf16((const bf16_t *)X, (const bf16_t *)W, (const bf16_t *)bias, (bf16_t *)Y,
                                                  (bf16_t *)X_proj, d->n, d->d_in, d->d_out, d->k, d->kind, st, ws, stream,
@@ -146,6 +146,7 @@ int forward_impl(const rmm_layer_desc_t *d, SketchState st, const void *X, const
                                            (const T *)bias, d->n, d->d_out, d->d_in, 1.0f, stream);
         if (e != hipSuccess) return RMM_ERR_LAUNCH;
     }
+    if (X_proj == nullptr) return RMM_OK;  // no backward pass will follow: nothing to keep
     StageScope scope(ev, RMM_STAGE_FWD_XPROJ, stream);
     return sketch_impl<T>(d->n, d->d_in, d->k, d->kind, st, X, X_proj, mfma, ws, stream, ev,
                           RMM_STAGE_FWD_XPROJ_PRODUCT);
@@ -201,7 +202,7 @@ int backward_impl(const rmm_layer_desc_t *d, SketchState st, const void *dY, con
 
 extern "C" {
 
-int rmm_version(void) { return 100; }
+int rmm_version(void) { return 200; }
 
 const char *rmm_status_string(int status) {
     switch (status) {
@@ -227,6 +228,13 @@ size_t rmm_workspace_bytes(const rmm_layer_desc_t *desc, int op) {
         case RMM_OP_VARIANCE: return ws_variance(&d);
         default: return 0;
     }
+}
+
+int rmm_uses_paired_launch(const rmm_layer_desc_t *desc, int op) {
+    if (!desc_ok(desc) || !use_mfma(desc)) return 0;
+    if (op == RMM_OP_FORWARD) return forward_pair_available(desc->n, desc->d_in, desc->d_out, desc->k) ? 1 : 0;
+    if (op == RMM_OP_BACKWARD) return backward_pair_available(desc->n, desc->d_in, desc->d_out, desc->k) ? 1 : 0;
+    return 0;
 }
 
 int rmm_sketch_profiled(int64_t n, int64_t d, int64_t k, int dtype, int kind, rmm_rng_state_t state, const void *A,
@@ -276,12 +284,11 @@ int rmm_sketch_static(int64_t n, int64_t d, int64_t k, int dtype, int kind, rmm_
 int rmm_forward_profiled(const rmm_layer_desc_t *desc, rmm_rng_state_t state, const void *X, const void *W,
                          const void *bias, void *Y, void *X_proj, void *ws, size_t ws_bytes, void *stream, int stage,
                          void *ev_begin, void *ev_end) {
-    if (!desc_ok(desc) || X == nullptr || W == nullptr || Y == nullptr || X_proj == nullptr)
-        return RMM_ERR_INVALID_ARG;
-    if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || !aligned16(X_proj) || !aligned16(ws))
+    if (!desc_ok(desc) || X == nullptr || W == nullptr || Y == nullptr) return RMM_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(W) || !aligned16(bias) || !aligned16(Y) || !aligned16(X_proj) || !aligned16(ws))
         return RMM_ERR_INVALID_ARG;
     if (!grid_ok(desc->n) || !grid_ok(desc->k)) return RMM_ERR_UNSUPPORTED;
-    const size_t need = ws_forward(desc);
+    const size_t need = X_proj != nullptr ? ws_forward(desc) : 0;
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return RMM_ERR_WORKSPACE;
     const SketchState st = make_state(state.seed, state.offset);
     hipStream_t s = (hipStream_t)stream;
@@ -304,7 +311,8 @@ static int backward_checked(const rmm_layer_desc_t *desc, rmm_rng_state_t state,
                             void *stream, int stage, void *ev_begin, void *ev_end, bool accumulate) {
     if (!desc_ok(desc) || dY == nullptr || W == nullptr || X_proj == nullptr || dW == nullptr)
         return RMM_ERR_INVALID_ARG;
-    if (!aligned16(dY) || !aligned16(W) || !aligned16(X_proj) || !aligned16(dX) || !aligned16(dW) || !aligned16(ws))
+    if (!aligned16(dY) || !aligned16(W) || !aligned16(X_proj) || !aligned16(dX) || !aligned16(dW) || !aligned16(dbias) ||
+        !aligned16(ws))
         return RMM_ERR_INVALID_ARG;
     if (!grid_ok(desc->n) || !grid_ok(desc->k) || !grid_ok(desc->d_out)) return RMM_ERR_UNSUPPORTED;
     const size_t need = ws_backward(desc);
@@ -344,6 +352,7 @@ int rmm_variance_stats(const rmm_layer_desc_t *desc, const void *X, const void *
                        size_t ws_bytes, void *stream) {
     if (!desc_ok(desc) || X == nullptr || dY == nullptr || out == nullptr) return RMM_ERR_INVALID_ARG;
     if (!aligned16(X) || !aligned16(dY) || !aligned16(ws) || ((uintptr_t)out & 7u) != 0) return RMM_ERR_INVALID_ARG;
+    if (!use_mfma(desc) && !grid_ok(desc->d_in)) return RMM_ERR_UNSUPPORTED;  // plain X^T dY: d_in rows of tiles
     if (ws == nullptr || ws_bytes < ws_variance(desc)) return RMM_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     const int nb = row_norm_blocks(desc->n), nt = var_xty_partials(desc);
@@ -384,7 +393,8 @@ int rmm_debug_sketch_tile(int kind, rmm_rng_state_t state, int64_t i0, int64_t j
                           float *P_out, void *stream) {
     if (P_out == nullptr || rows < 1 || cols < 1 || i0 < 0 || j0 < 0) return RMM_ERR_INVALID_ARG;
     if (kind != RMM_SKETCH_GAUSSIAN && kind != RMM_SKETCH_RADEMACHER) return RMM_ERR_INVALID_ARG;
-    if (!dims_ok(rows, cols) || i0 + rows > kMaxDim || j0 + cols > kMaxDim) return RMM_ERR_UNSUPPORTED;
+    if (!dims_ok(rows, cols) || rows * cols > kMaxDim || i0 + rows > kMaxDim || j0 + cols > kMaxDim)
+        return RMM_ERR_UNSUPPORTED;  // one thread per entry, 2^23 work-groups at most
     return from_hip(launch_debug_sketch_tile(kind, make_state(state.seed, state.offset), i0, j0, rows, cols, P_out,
                                              (hipStream_t)stream));
 }

@@ -4,9 +4,13 @@
 Argument marshalling only: the forward is one `rmm_forward` call, the backward one
 `rmm_backward` call; autograd keeps X_proj and the 16-byte sketch state, not X (Section 2.4.1).
 """
+import itertools
+
 import torch
 
 from . import binding
+
+_layer_ids = itertools.count()     # process-wide: layers built without an explicit layer_id get distinct ones
 
 
 class RMMLinearFunction(torch.autograd.Function):
@@ -41,14 +45,18 @@ class RMMLinearFunction(torch.autograd.Function):
 
 class RMMLinear(torch.nn.Module):
     """`nn.Linear` replacement.  The sketch size is `k` tokens, or `round(rho * n)` of the n
-    tokens of each call (clamped to [1, n]); every forward call draws a fresh sketch: state
-    (seed, offset = layer_id * 2^32 + call counter), as the independence of S from dY needs."""
+    tokens of each call (clamped to [1, n]); every forward call that will be followed by a
+    backward call draws a fresh sketch: state (seed, offset = layer_id * 2^32 + call counter), so
+    that sketches of different layers and steps are independent of each other and of dY
+    (Section 2.1).  `layer_id` defaults to a process-wide running number.  With gradients disabled
+    the layer computes Y only: no sketch, no state consumed."""
 
     def __init__(self, in_features, out_features, bias=True, rho=0.1, k=None, kind=binding.GAUSSIAN, seed=0,
-                 layer_id=0, device="cuda", dtype=torch.bfloat16):
+                 layer_id=None, device="cuda", dtype=torch.bfloat16):
         super().__init__()
         self.in_features, self.out_features = in_features, out_features
-        self.rho, self.k, self.kind, self.seed, self.layer_id = rho, k, kind, seed, layer_id
+        self.rho, self.k, self.kind, self.seed = rho, k, kind, seed
+        self.layer_id = next(_layer_ids) if layer_id is None else int(layer_id)
         self.calls = 0
         self.weight = torch.nn.Parameter(torch.empty((out_features, in_features), device=device, dtype=dtype))
         self.bias = torch.nn.Parameter(torch.zeros((out_features,), device=device, dtype=dtype)) if bias else None
@@ -65,6 +73,11 @@ class RMMLinear(torch.nn.Module):
 
     def forward(self, X):
         n = X.numel() // X.shape[-1]
+        if not torch.is_grad_enabled():        # nothing will be kept for a backward pass: Y alone
+            X2 = X.reshape(-1, X.shape[-1]).contiguous()
+            Y, _ = binding.rmm_forward(X2, self.weight.detach().contiguous(), self.bias, 1, self.kind, 0, 0,
+                                       need_xproj=False)
+            return Y.reshape(*X.shape[:-1], self.out_features)
         seed, offset = self.next_state()
         self.last_state = (seed, offset)
         return RMMLinearFunction.apply(X, self.weight, self.bias, self.sketch_size(n), self.kind, seed, offset)

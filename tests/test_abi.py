@@ -70,6 +70,10 @@ def test_invalid_arguments_are_status_codes(lib):
         assert lib.rmm_forward(ctypes.byref(bad), st, fake, fake, None, fake, fake, None, 0, None) == -1
         assert lib.rmm_backward(ctypes.byref(bad), st, fake, fake, fake, fake, fake, None, None, 0, None) == -1
     assert lib.rmm_backward(ctypes.byref(good), st, fake, fake, fake, fake, None, None, None, 0, None) == -1
+    # bias / dbias are read and written with vector accesses: a misaligned one is refused
+    assert lib.rmm_forward(ctypes.byref(good), st, fake, fake, odd, fake, fake, None, 0, None) == -1
+    assert lib.rmm_backward(ctypes.byref(good), st, fake, fake, fake, fake, fake, odd, fake, 1 << 20, None) == -1
+    assert lib.rmm_backward_accumulate(ctypes.byref(good), st, fake, fake, fake, fake, fake, odd, fake, 1 << 20, None) == -1
     # workspace missing / too small
     assert lib.rmm_backward(ctypes.byref(good), st, fake, fake, fake, fake, fake, None, None, 0, None) == -3
     assert lib.rmm_backward(ctypes.byref(good), st, fake, fake, fake, fake, fake, None, fake, 8, None) == -3
@@ -80,6 +84,10 @@ def test_invalid_arguments_are_status_codes(lib):
     assert lib.rmm_debug_philox(st, 0, 0, 4, None, None) == -1
     assert lib.rmm_debug_sketch_tile(0, st, -1, 0, 4, 4, fake, None) == -1
     assert lib.rmm_debug_sketch_tile(2, st, 0, 0, 4, 4, fake, None) == -1
+    assert lib.rmm_debug_sketch_tile(0, st, 0, 0, 1 << 20, 1 << 12, fake, None) == -2      # more entries than one launch covers
+    # variance monitors off the MFMA path: d_in sets the number of tile rows of the plain product
+    wide = D(8, (1 << 22) + 4, 8, 2, 0, 0)
+    assert lib.rmm_variance_stats(ctypes.byref(wide), fake, fake, fake, fake, 1 << 40, None) == -2
 
 
 def test_binding_refuses_cpu_tensors(lib):

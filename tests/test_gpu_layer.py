@@ -108,3 +108,25 @@ def test_two_layer_mlp_trains_with_sketched_weight_gradients():
     assert all(np.isfinite(sketched)) and abs(sketched[0] - exact[0]) < 1e-4 * exact[0]
     assert sketched[-1] < 0.6 * sketched[0] and sketched[-1] < 1.5 * exact[-1]
     assert l1.calls == 200 and l2.last_state == (1, (1 << 32) | 199)
+
+
+def test_default_layers_draw_independent_sketches_and_no_grad_skips_the_sketch():
+    """Two layers built with default arguments must not share a sketch (Section 2.1: S of
+    different layers independent): their saved X_proj differ for the same input.  Under
+    torch.no_grad() the layer returns the same Y and consumes no sketch state."""
+    n, d_in, d_out = 384, 96, 64
+    X, W, _ = synth.layer_inputs(n, d_in, d_out, "bf16", (91, 92, 93))
+    a, b = rmm.RMMLinear(d_in, d_out, bias=False, k=48), rmm.RMMLinear(d_in, d_out, bias=False, k=48)
+    assert a.layer_id != b.layer_id
+    with torch.no_grad():
+        a.weight.copy_(W.to(DEV)), b.weight.copy_(W.to(DEV))
+    Xd = X.to(DEV).requires_grad_(True)
+    Ya, Yb = a(Xd), b(Xd)
+    assert torch.equal(Ya, Yb)                                          # Y does not depend on the sketch
+    Xpa = rmm.rmm_sketch(X.to(DEV), 48, a.kind, *a.last_state)
+    Xpb = rmm.rmm_sketch(X.to(DEV), 48, b.kind, *b.last_state)
+    assert a.last_state != b.last_state and not torch.equal(Xpa, Xpb)
+    calls = a.calls
+    with torch.no_grad():
+        Y0 = a(X.to(DEV))
+    assert a.calls == calls and torch.equal(Y0, Ya.detach())
