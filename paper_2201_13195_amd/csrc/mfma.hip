@@ -78,15 +78,16 @@ GemmArgs args_nn(const bf16_t *dY, const bf16_t *W, bf16_t *dX, int64_t n, int64
 //                            instead of 512);
 //   d a multiple of 384:     the same with 384-column tiles (d = 768);
 //   other d below 1024:      128 x 256 tiles whose sketch fragments are generated in registers.
-// Tokens are cut into `splits` slices of `k_chunk` tokens (a multiple of 128) so that about 256
-// work-groups exist; with more than one slice the kernel writes fp32 partial results to workspace
-// and reduce_partials_kernel sums them in slice order.
+// Tokens are cut into `splits` slices of `k_chunk` tokens (a multiple of 128) so that about
+// `target_wgs` work-groups exist (256 = one per compute unit; measured: more or fewer are slower
+// when the product runs alone); with more than one slice the kernel writes fp32 partial results
+// to workspace and reduce_partials_kernel sums them in slice order.
 struct SketchPlan {
     int cfg, splits;
     int64_t k_chunk, tiles;
 };
 
-SketchPlan plan_sketch(int64_t n, int64_t d, int64_t k) {
+SketchPlan plan_sketch(int64_t n, int64_t d, int64_t k, int target_wgs = 256) {
     SketchPlan p;
     const bool rows64 = k <= 512;
     p.cfg = d >= 1024 ? (rows64 ? SK_WIDE64 : SK_WIDE) : d % 384 == 0 ? (rows64 ? SK_MID64 : SK_MID) : SK_NARROW;
@@ -94,7 +95,7 @@ SketchPlan plan_sketch(int64_t n, int64_t d, int64_t k) {
     const int64_t bn = p.cfg == SK_NARROW ? 256 : (p.cfg == SK_MID64 || p.cfg == SK_MID) ? 384 : 512;
     p.tiles = tiles_of(k, d, bm, bn);
     const int64_t blocks = (n + 127) / 128;
-    int64_t s = 256 / p.tiles;
+    int64_t s = target_wgs / p.tiles;
     if (s > blocks) s = blocks;
     if (s > 64) s = 64;
     if (s < 1) s = 1;
@@ -189,6 +190,31 @@ bool pair_ok(int cfg_a, int depth_a, const SketchPlan &p, bool nn) {
     return nn && cfg_a == GEMM_SPLIT && depth_a == 4;
 }
 
+// Work-groups the sketch product of a pass should aim at when it is launched together with the
+// pass's plain product (`blocks_a` tiles, flops_a flop): if the plain product leaves compute units
+// idle in its last round and runs long enough for the whole sketch product (flops_sk, at about half
+// the plain product's rate per compute unit) to finish on them, one work-group per idle compute
+// unit (fewer, longer work-groups: less prologue, fewer partial sums); otherwise 256.
+int paired_sketch_target(int64_t blocks_a, double flops_a, double flops_sk) {
+    const int64_t idle = (256 - blocks_a % 256) % 256;
+    if (idle >= 32 && 2.0 * flops_sk * (double)blocks_a <= (double)idle * flops_a) return (int)idle;
+    return 256;
+}
+
+// Plan of the sketch product of X (forward) / dY (backward) inside a layer call.
+SketchPlan plan_pass_sketch(int64_t n, int64_t d_sk, int64_t d_other, int64_t k, bool nn) {
+    // the plain product has an n x d_other output and contracts over d_sk
+    const SketchPlan alone = plan_sketch(n, d_sk, k);
+    const int cfg_a = gemm_cfg(n, d_other, d_sk);
+    const int depth_a = cfg_a == GEMM_SPLIT ? plain_depth(d_sk, ShapeSplit::BK) : 3;
+    if (!pair_ok(cfg_a, depth_a, alone, nn)) return alone;
+    const int64_t blocks_a = cfg_a == GEMM_LARGE ? tiles_of(n, d_other, ShapeLarge::BM, ShapeLarge::BN)
+                                                 : tiles_of(n, d_other, ShapeSplit::BM, ShapeSplit::BN);
+    const int target = paired_sketch_target(blocks_a, 2.0 * n * d_sk * d_other, 2.0 * n * k * d_sk);
+    const SketchPlan paired = plan_sketch(n, d_sk, k, target);
+    return paired.splits >= 2 ? paired : alone;
+}
+
 }  // namespace
 
 bool mfma_shape_ok(int64_t n, int64_t d_in, int64_t d_out, int64_t k) {
@@ -242,14 +268,16 @@ hipError_t launch_xty_sumsq_bf16(const bf16_t *X, const bf16_t *dY, double *part
     return launch_gemm<A_MCONTIG, B_NCONTIG, OUT_SUMSQ>(xty_cfg(g.M, g.N, g.K), g, stream);
 }
 
-size_t sketch_workspace_bf16(int64_t n, int64_t d, int64_t k) {
+size_t sketch_workspace_bf16(int64_t n, int64_t d, int64_t k, int64_t d_other, bool backward) {
     int64_t k_chunk;
-    const int s = k <= kSmallK ? smallk_slices(n, d, &k_chunk) : plan_sketch(n, d, k).splits;
+    const int s = k <= kSmallK ? smallk_slices(n, d, &k_chunk)
+                               : (d_other > 0 ? plan_pass_sketch(n, d, d_other, k, backward) : plan_sketch(n, d, k)).splits;
     return s > 1 ? (size_t)s * (size_t)k * (size_t)d * sizeof(float) : 0;
 }
 
 hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d, int64_t k, int kind, SketchState st,
-                              void *ws, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end) {
+                              void *ws, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end, int64_t d_other,
+                              bool backward) {
     EventPair pev(ev_begin, ev_end, stream);
     if (k <= kSmallK) {  // bound by one pass over A: streaming kernel
         SmallkArgs a{};
@@ -262,7 +290,7 @@ hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d
         if (e != hipSuccess || slices == 1) return e;
         return launch_reduce(ws, out, k, d, slices, stream);
     }
-    const SketchPlan p = plan_sketch(n, d, k);
+    const SketchPlan p = d_other > 0 ? plan_pass_sketch(n, d, d_other, k, backward) : plan_sketch(n, d, k);
     const GemmArgs g = args_sketch(A, n, d, k, st, p, out, ws);
     if (p.splits == 1) return launch_sketch_cfg<OUT_BF16>(p.cfg, kind, g, 1, stream);
     hipError_t e = launch_sketch_cfg<OUT_F32_PARTIAL>(p.cfg, kind, g, p.splits, stream);
@@ -273,14 +301,14 @@ hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d
 
 bool forward_pair_available(int64_t n, int64_t d_in, int64_t d_out, int64_t k) {
     if (k <= kSmallK) return false;
-    return pair_ok(gemm_cfg(n, d_out, d_in), 3, plan_sketch(n, d_in, k), false);
+    return pair_ok(gemm_cfg(n, d_out, d_in), 3, plan_sketch(n, d_in, k), false);  // the paired plan keeps >= 2 slices
 }
 
 hipError_t launch_forward_pair_bf16(const bf16_t *X, const bf16_t *W, const bf16_t *bias, bf16_t *Y, bf16_t *X_proj,
                                     int64_t n, int64_t d_in, int64_t d_out, int64_t k, int kind, SketchState st, void *ws,
                                     hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end) {
     const GemmArgs ga = args_nt(X, W, bias, Y, n, d_in, d_out);
-    const SketchPlan p = plan_sketch(n, d_in, k);
+    const SketchPlan p = plan_pass_sketch(n, d_in, d_out, k, false);
     const GemmArgs gb = args_sketch(X, n, d_in, k, st, p, X_proj, ws);
     EventPair pev(ev_begin, ev_end, stream);
     const int blocks_a = (int)tiles_of(ga.M, ga.N, ShapeLarge::BM, ShapeLarge::BN);
@@ -300,7 +328,7 @@ hipError_t launch_backward_pair_bf16(const bf16_t *dY, const bf16_t *W, bf16_t *
                                      int64_t d_out, int64_t k, int kind, SketchState st, void *ws, hipStream_t stream,
                                      hipEvent_t ev_begin, hipEvent_t ev_end) {
     const GemmArgs ga = args_nn(dY, W, dX, n, d_in, d_out);
-    const SketchPlan p = plan_sketch(n, d_out, k);
+    const SketchPlan p = plan_pass_sketch(n, d_out, d_in, k, true);
     const GemmArgs gb = args_sketch(dY, n, d_out, k, st, p, G, ws);
     EventPair pev(ev_begin, ev_end, stream);
     hipError_t e;
