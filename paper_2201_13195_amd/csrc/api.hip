@@ -44,10 +44,10 @@ size_t ws_sketch(const rmm_layer_desc_t *d) {
     return use_mfma(d) ? round_up(sketch_workspace_bf16(d->n, d->d_in, d->k), 256) : 0;
 }
 size_t ws_forward(const rmm_layer_desc_t *d) {
-    return use_mfma(d) ? round_up(sketch_workspace_bf16(d->n, d->d_in, d->k, d->d_out, false), 256) : 0;
+    return use_mfma(d) ? round_up(sketch_workspace_bf16(d->n, d->d_in, d->k, d->d_out), 256) : 0;
 }
 size_t ws_backward(const rmm_layer_desc_t *d) {
-    return g_bytes(d) + (use_mfma(d) ? round_up(sketch_workspace_bf16(d->n, d->d_out, d->k, d->d_in, true), 256) : 0);
+    return g_bytes(d) + (use_mfma(d) ? round_up(sketch_workspace_bf16(d->n, d->d_out, d->k, d->d_in), 256) : 0);
 }
 
 // variance monitors: per-block partials (doubles), then, off the MFMA path, X^T dY in fp32.
@@ -120,11 +120,11 @@ private:
 template <typename T>
 int sketch_impl(int64_t n, int64_t d, int64_t k, int kind, SketchState st, const void *A, void *out, bool mfma,
                 void *ws, hipStream_t stream, const StageEvents &ev = StageEvents(), int product_stage = RMM_STAGE_NONE,
-                int64_t d_other = 0, bool backward = false) {
+                int64_t d_other = 0) {
     const bool timed = product_stage != RMM_STAGE_NONE && ev.stage == product_stage;
     if (mfma)
         return from_hip(launch_sketch_bf16((const bf16_t *)A, (bf16_t *)out, n, d, k, kind, st, ws, stream,
-                                           timed ? ev.begin : nullptr, timed ? ev.end : nullptr, d_other, backward));
+                                           timed ? ev.begin : nullptr, timed ? ev.end : nullptr, d_other));
     StageScope scope(ev, product_stage, stream);  // the plain path is one kernel
     const float alpha = 1.0f / sqrtf((float)k);
     return from_hip(launch_sketch_plain<T, T>((const T *)A, (T *)out, n, d, k, kind, st, alpha, stream));
@@ -152,7 +152,7 @@ int forward_impl(const rmm_layer_desc_t *d, SketchState st, const void *X, const
     if (X_proj == nullptr) return RMM_OK;  // no backward pass will follow: nothing to keep
     StageScope scope(ev, RMM_STAGE_FWD_XPROJ, stream);
     return sketch_impl<T>(d->n, d->d_in, d->k, d->kind, st, X, X_proj, mfma, ws, stream, ev,
-                          RMM_STAGE_FWD_XPROJ_PRODUCT, d->d_out, false);
+                          RMM_STAGE_FWD_XPROJ_PRODUCT, d->d_out);
 }
 
 template <typename T>
@@ -182,7 +182,7 @@ int backward_impl(const rmm_layer_desc_t *d, SketchState st, const void *dY, con
     if (!paired) {
         StageScope scope(ev, RMM_STAGE_BWD_G, stream);
         int rc = sketch_impl<T>(d->n, d->d_out, d->k, d->kind, st, dY, G, mfma, (char *)ws + g_bytes(d), stream, ev,
-                                RMM_STAGE_BWD_G_PRODUCT, d->d_in, true);
+                                RMM_STAGE_BWD_G_PRODUCT, d->d_in);
         if (rc != RMM_OK) return rc;
     }
     {   // dW = G^T X_proj: A(r, kk) = G[kk][r], B(kk, c) = X_proj[kk][c]

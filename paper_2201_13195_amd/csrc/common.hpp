@@ -67,10 +67,10 @@ hipError_t launch_dw_bf16(const bf16_t *G, const bf16_t *X_proj, bf16_t *dW, int
 // n x d_other output (forward: d = d_in, d_other = d_out; backward: d = d_out, d_other = d_in): the
 // token slicing is then the one the paired launch of that pass uses, so that the separate and the
 // paired launches give the same bits.  0 = the product on its own (rmm_sketch).
-size_t sketch_workspace_bf16(int64_t n, int64_t d, int64_t k, int64_t d_other = 0, bool backward = false);
+size_t sketch_workspace_bf16(int64_t n, int64_t d, int64_t k, int64_t d_other = 0);
 hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d, int64_t k, int kind, SketchState st,
                               void *ws, hipStream_t stream, hipEvent_t ev_begin = nullptr,
-                              hipEvent_t ev_end = nullptr, int64_t d_other = 0, bool backward = false);
+                              hipEvent_t ev_end = nullptr, int64_t d_other = 0);
 
 // One launch for the two products of a pass that do not depend on each other: Y = X W^T (+ bias)
 // with the sketch product of X (forward), dX = dY W with the sketch product of dY (backward; G is

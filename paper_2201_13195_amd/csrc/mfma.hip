@@ -181,13 +181,12 @@ struct EventPair {
     ~EventPair() { done(); }
 };
 
-// The paired launch exists for a plain product on 256 x 256 tiles, or (dX only) on the
-// 128 x 128 x 64 split tiles at prefetch depth 4, next to a sketch product with an LDS-generated
-// tile and at least two token slices.
-bool pair_ok(int cfg_a, int depth_a, const SketchPlan &p, bool nn) {
+// The paired launch exists for a plain product on 256 x 256 tiles, or on the 128 x 128 x 64 split
+// tiles at prefetch depth 4 (both run with 512 threads, like the sketch kernels), next to a sketch
+// product with an LDS-generated tile and at least two token slices.
+bool pair_ok(int cfg_a, int depth_a, const SketchPlan &p) {
     if (p.cfg == SK_NARROW || p.splits < 2) return false;
-    if (cfg_a == GEMM_LARGE) return true;
-    return nn && cfg_a == GEMM_SPLIT && depth_a == 4;
+    return cfg_a == GEMM_LARGE || (cfg_a == GEMM_SPLIT && depth_a == 4);
 }
 
 // Work-groups the sketch product of a pass should aim at when it is launched together with the
@@ -202,12 +201,12 @@ int paired_sketch_target(int64_t blocks_a, double flops_a, double flops_sk) {
 }
 
 // Plan of the sketch product of X (forward) / dY (backward) inside a layer call.
-SketchPlan plan_pass_sketch(int64_t n, int64_t d_sk, int64_t d_other, int64_t k, bool nn) {
+SketchPlan plan_pass_sketch(int64_t n, int64_t d_sk, int64_t d_other, int64_t k) {
     // the plain product has an n x d_other output and contracts over d_sk
     const SketchPlan alone = plan_sketch(n, d_sk, k);
     const int cfg_a = gemm_cfg(n, d_other, d_sk);
     const int depth_a = cfg_a == GEMM_SPLIT ? plain_depth(d_sk, ShapeSplit::BK) : 3;
-    if (!pair_ok(cfg_a, depth_a, alone, nn)) return alone;
+    if (!pair_ok(cfg_a, depth_a, alone)) return alone;
     const int64_t blocks_a = cfg_a == GEMM_LARGE ? tiles_of(n, d_other, ShapeLarge::BM, ShapeLarge::BN)
                                                  : tiles_of(n, d_other, ShapeSplit::BM, ShapeSplit::BN);
     const int target = paired_sketch_target(blocks_a, 2.0 * n * d_sk * d_other, 2.0 * n * k * d_sk);
@@ -268,16 +267,15 @@ hipError_t launch_xty_sumsq_bf16(const bf16_t *X, const bf16_t *dY, double *part
     return launch_gemm<A_MCONTIG, B_NCONTIG, OUT_SUMSQ>(xty_cfg(g.M, g.N, g.K), g, stream);
 }
 
-size_t sketch_workspace_bf16(int64_t n, int64_t d, int64_t k, int64_t d_other, bool backward) {
+size_t sketch_workspace_bf16(int64_t n, int64_t d, int64_t k, int64_t d_other) {
     int64_t k_chunk;
     const int s = k <= kSmallK ? smallk_slices(n, d, &k_chunk)
-                               : (d_other > 0 ? plan_pass_sketch(n, d, d_other, k, backward) : plan_sketch(n, d, k)).splits;
+                               : (d_other > 0 ? plan_pass_sketch(n, d, d_other, k) : plan_sketch(n, d, k)).splits;
     return s > 1 ? (size_t)s * (size_t)k * (size_t)d * sizeof(float) : 0;
 }
 
 hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d, int64_t k, int kind, SketchState st,
-                              void *ws, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end, int64_t d_other,
-                              bool backward) {
+                              void *ws, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end, int64_t d_other) {
     EventPair pev(ev_begin, ev_end, stream);
     if (k <= kSmallK) {  // bound by one pass over A: streaming kernel
         SmallkArgs a{};
@@ -290,7 +288,7 @@ hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d
         if (e != hipSuccess || slices == 1) return e;
         return launch_reduce(ws, out, k, d, slices, stream);
     }
-    const SketchPlan p = d_other > 0 ? plan_pass_sketch(n, d, d_other, k, backward) : plan_sketch(n, d, k);
+    const SketchPlan p = d_other > 0 ? plan_pass_sketch(n, d, d_other, k) : plan_sketch(n, d, k);
     const GemmArgs g = args_sketch(A, n, d, k, st, p, out, ws);
     if (p.splits == 1) return launch_sketch_cfg<OUT_BF16>(p.cfg, kind, g, 1, stream);
     hipError_t e = launch_sketch_cfg<OUT_F32_PARTIAL>(p.cfg, kind, g, p.splits, stream);
@@ -301,18 +299,24 @@ hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d
 
 bool forward_pair_available(int64_t n, int64_t d_in, int64_t d_out, int64_t k) {
     if (k <= kSmallK) return false;
-    return pair_ok(gemm_cfg(n, d_out, d_in), 3, plan_sketch(n, d_in, k), false);  // the paired plan keeps >= 2 slices
+    const int cfg = gemm_cfg(n, d_out, d_in);  // (the paired plan keeps >= 2 slices)
+    return pair_ok(cfg, cfg == GEMM_SPLIT ? plain_depth(d_in, ShapeSplit::BK) : 3, plan_sketch(n, d_in, k));
 }
 
 hipError_t launch_forward_pair_bf16(const bf16_t *X, const bf16_t *W, const bf16_t *bias, bf16_t *Y, bf16_t *X_proj,
                                     int64_t n, int64_t d_in, int64_t d_out, int64_t k, int kind, SketchState st, void *ws,
                                     hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end) {
     const GemmArgs ga = args_nt(X, W, bias, Y, n, d_in, d_out);
-    const SketchPlan p = plan_pass_sketch(n, d_in, d_out, k, false);
+    const SketchPlan p = plan_pass_sketch(n, d_in, d_out, k);
     const GemmArgs gb = args_sketch(X, n, d_in, k, st, p, X_proj, ws);
     EventPair pev(ev_begin, ev_end, stream);
-    const int blocks_a = (int)tiles_of(ga.M, ga.N, ShapeLarge::BM, ShapeLarge::BN);
-    hipError_t e = launch_pair_nt(p.cfg, kind, ga, gb, blocks_a, (int)p.tiles, p.splits, stream);
+    hipError_t e;
+    if (gemm_cfg(ga.M, ga.N, ga.K) == GEMM_LARGE)
+        e = launch_pair_nt(p.cfg, kind, ga, gb, (int)tiles_of(ga.M, ga.N, ShapeLarge::BM, ShapeLarge::BN), (int)p.tiles,
+                           p.splits, stream);
+    else
+        e = launch_pair_nt_split(p.cfg, kind, ga, gb, (int)tiles_of(ga.M, ga.N, ShapeSplit::BM, ShapeSplit::BN), (int)p.tiles,
+                                 p.splits, stream);
     pev.done();
     if (e != hipSuccess) return e;
     return launch_reduce(ws, X_proj, k, d_in, p.splits, stream);
@@ -321,14 +325,14 @@ hipError_t launch_forward_pair_bf16(const bf16_t *X, const bf16_t *W, const bf16
 bool backward_pair_available(int64_t n, int64_t d_in, int64_t d_out, int64_t k) {
     if (k <= kSmallK) return false;
     const int cfg = gemm_cfg(n, d_in, d_out);
-    return pair_ok(cfg, cfg == GEMM_SPLIT ? plain_depth(d_out, ShapeSplit::BK) : 3, plan_sketch(n, d_out, k), true);
+    return pair_ok(cfg, cfg == GEMM_SPLIT ? plain_depth(d_out, ShapeSplit::BK) : 3, plan_sketch(n, d_out, k));
 }
 
 hipError_t launch_backward_pair_bf16(const bf16_t *dY, const bf16_t *W, bf16_t *dX, bf16_t *G, int64_t n, int64_t d_in,
                                      int64_t d_out, int64_t k, int kind, SketchState st, void *ws, hipStream_t stream,
                                      hipEvent_t ev_begin, hipEvent_t ev_end) {
     const GemmArgs ga = args_nn(dY, W, dX, n, d_in, d_out);
-    const SketchPlan p = plan_pass_sketch(n, d_out, d_in, k, true);
+    const SketchPlan p = plan_pass_sketch(n, d_out, d_in, k);
     const GemmArgs gb = args_sketch(dY, n, d_out, k, st, p, G, ws);
     EventPair pev(ev_begin, ev_end, stream);
     hipError_t e;

@@ -13,11 +13,14 @@ enum { SK_NARROW = 0, SK_WIDE = 1, SK_WIDE64 = 2, SK_MID64 = 3, SK_MID = 4 };
 // One launch for a plain product (`ga`, `blocks_a` tiles) and a sketch product with an
 // LDS-generated tile (`gb`, `tiles_b` tiles x `splits` token slices, fp32 partial results).
 //   nt:       Y = X W^T, 256 x 256 tiles (GEMM_LARGE, prefetch depth 3)
+//   nt_split: Y = X W^T, 128 x 128 x 64 tiles with two wave groups (GEMM_SPLIT, depth 4)
 //   nn_large: dX = dY W, 256 x 256 tiles (GEMM_LARGE, depth 3)
 //   nn_split: dX = dY W, 128 x 128 x 64 tiles with two wave groups (GEMM_SPLIT, depth 4)
 // sk_cfg is one of SK_WIDE, SK_WIDE64, SK_MID64, SK_MID; anything else returns hipErrorInvalidValue.
 hipError_t launch_pair_nt(int sk_cfg, int kind, const GemmArgs &ga, const GemmArgs &gb, int blocks_a, int tiles_b,
                           int splits, hipStream_t stream);
+hipError_t launch_pair_nt_split(int sk_cfg, int kind, const GemmArgs &ga, const GemmArgs &gb, int blocks_a, int tiles_b,
+                                int splits, hipStream_t stream);
 hipError_t launch_pair_nn_large(int sk_cfg, int kind, const GemmArgs &ga, const GemmArgs &gb, int blocks_a, int tiles_b,
                                 int splits, hipStream_t stream);
 hipError_t launch_pair_nn_split(int sk_cfg, int kind, const GemmArgs &ga, const GemmArgs &gb, int blocks_a, int tiles_b,

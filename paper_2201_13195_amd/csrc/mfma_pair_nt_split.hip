@@ -1,0 +1,11 @@
+// Paired-launch kernels (see mfma_pair.hpp): launch_pair_nt_split.
+#include "mfma_pair.hpp"
+
+namespace rmm {
+
+hipError_t launch_pair_nt_split(int sk_cfg, int kind, const GemmArgs &ga, const GemmArgs &gb, int blocks_a, int tiles_b,
+                            int splits, hipStream_t stream) {
+    return launch_pair_impl<ShapeSplit, B_KCONTIG, 4>(sk_cfg, kind, ga, gb, blocks_a, tiles_b, splits, stream);
+}
+
+}  // namespace rmm
