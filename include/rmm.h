@@ -42,7 +42,7 @@
  *              gives words r0..r3; w = r[(i mod 8) div 2];
  *              u1 = ((w div 2^16) + 1/2) / 2^16, u2 = (w mod 2^16) / 2^16;
  *              P = sqrt(-2 ln u1) * (cos(2 pi u2) if i even, sin(2 pi u2) if i odd).
- *   Rademacher (Section 3.4): call counter (i div 128, j, offset lo, offset hi);
+ *   Rademacher (Section 3.5): call counter (i div 128, j, offset lo, offset hi);
  *              t = i mod 128; bit = (r[t div 32] >> (t mod 32)) & 1; P = 1 - 2 bit.
  * Entries do not depend on n or k, so a forward and a backward call that pass
  * the same state, k and kind see the same S (Algorithm 1, "rematerialize S").
