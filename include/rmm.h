@@ -44,8 +44,22 @@
  *              P = sqrt(-2 ln u1) * (cos(2 pi u2) if i even, sin(2 pi u2) if i odd).
  *   Rademacher (Section 3.5): call counter (i div 128, j, offset lo, offset hi);
  *              t = i mod 128; bit = (r[t div 32] >> (t mod 32)) & 1; P = 1 - 2 bit.
- * Entries do not depend on n or k, so a forward and a backward call that pass
- * the same state, k and kind see the same S (Algorithm 1, "rematerialize S").
+ *   SORS       (subsampled orthonormal matrix with random signs: Section 2.1 names the family,
+ *              Section 3.5 and the future-work paragraph its O(B N log B) product; the paper gives
+ *              no construction, this one is the subsampled randomized Walsh-Hadamard transform):
+ *              n_pad = smallest power of two >= n;
+ *              sigma_i = the Rademacher entry of token i for the column number 0xFFFFFFFF;
+ *              r_j = word (j mod 4) of call counter (j div 4, 0xFFFFFFFE, offset lo, offset hi)
+ *              AND (n_pad - 1);   P = sigma_i * (-1)^popcount(i AND r_j).
+ *              So S^T A = sqrt(n_pad / k) * R H D [A; 0]: D = diag(sigma), H the orthonormal
+ *              Walsh-Hadamard matrix in Sylvester order, R the selection of rows r_0 .. r_{k-1}
+ *              (uniform, independent, with replacement), and E[S S^T] = I.  bf16 with d a multiple
+ *              of 8 and n <= 32768 runs the fast transform (one pass over A); other cases apply the
+ *              same S entry by entry (correct, O(n k d)).  rmm_variance_stats has no closed form
+ *              for this kind (RMM_ERR_UNSUPPORTED).
+ * Entries of the Gaussian and Rademacher kinds do not depend on n or k (SORS entries depend on n
+ * through n_pad), so a forward and a backward call that pass
+ * the same state, n, k and kind see the same S (Algorithm 1, "rematerialize S").
  * The caller must use a fresh offset for every forward call so that sketches of
  * different layers and steps are independent of each other and of dY
  * (Section 2.1, the independence requirement below Eq. 4).
@@ -70,7 +84,7 @@ typedef enum {
 } rmm_status_t;
 
 typedef enum { RMM_DTYPE_F32 = 0, RMM_DTYPE_BF16 = 1 } rmm_dtype_t;
-typedef enum { RMM_SKETCH_GAUSSIAN = 0, RMM_SKETCH_RADEMACHER = 1 } rmm_sketch_kind_t;
+typedef enum { RMM_SKETCH_GAUSSIAN = 0, RMM_SKETCH_RADEMACHER = 1, RMM_SKETCH_SORS = 2 } rmm_sketch_kind_t;
 typedef enum { RMM_OP_FORWARD = 0, RMM_OP_BACKWARD = 1, RMM_OP_SKETCH = 2, RMM_OP_VARIANCE = 3 } rmm_op_t;
 
 /* The "PRNG state" saved between forward and backward (Algorithm 1): 16 bytes. */

@@ -5,7 +5,7 @@ include/rmm.h).  This package only marshals arguments: PyTorch tensors supply
 device memory and the current stream.
 """
 from .binding import (  # noqa: F401
-    GAUSSIAN, RADEMACHER, RmmError, lib_path, load_library, rmm_backward, rmm_debug_philox,
+    GAUSSIAN, RADEMACHER, SORS, RmmError, lib_path, load_library, rmm_backward, rmm_debug_philox,
     rmm_debug_sketch_tile, rmm_forward, rmm_probe_mfma, rmm_probe_read, rmm_uses_paired_launch, rmm_sketch, rmm_sketch_static, rmm_status_string, rmm_variance_stats, rmm_version, rmm_workspace_bytes,
     STATIC_SCRATCH_BYTES, VARIANCE_FIELDS,
 )

@@ -8,6 +8,7 @@ import torch
 
 GAUSSIAN = 0
 RADEMACHER = 1
+SORS = 2
 OP_FORWARD, OP_BACKWARD, OP_SKETCH, OP_VARIANCE = 0, 1, 2, 3
 _DTYPES = {torch.float32: 0, torch.bfloat16: 1}
 

@@ -24,7 +24,7 @@ bool dims_ok(int64_t a, int64_t b) { return a >= 1 && b >= 1 && a < kMaxDim && b
 bool desc_ok(const rmm_layer_desc_t *d) {
     if (d == nullptr) return false;
     if (d->dtype != RMM_DTYPE_F32 && d->dtype != RMM_DTYPE_BF16) return false;
-    if (d->kind != RMM_SKETCH_GAUSSIAN && d->kind != RMM_SKETCH_RADEMACHER) return false;
+    if (d->kind != RMM_SKETCH_GAUSSIAN && d->kind != RMM_SKETCH_RADEMACHER && d->kind != RMM_SKETCH_SORS) return false;
     return dims_ok(d->n, d->d_in) && dims_ok(d->n, d->d_out) && dims_ok(d->d_out, d->d_in) &&
            dims_ok(d->k, d->d_in) && dims_ok(d->k, d->d_out) && dims_ok(d->n, d->k);
 }
@@ -40,14 +40,16 @@ bool use_mfma(const rmm_layer_desc_t *d) {
 //   sketch / forward: fp32 partial sums of the token slices of S^T A (MFMA path only).
 //   backward: G = S^T dY (k x d_out, in the layer's dtype), then the partial sums.
 size_t g_bytes(const rmm_layer_desc_t *d) { return round_up((size_t)d->k * d->d_out * elem_bytes(d->dtype), 256); }
+// (the SORS kind has no token slices: its sketch products need no scratch)
+bool sliced_sketch(const rmm_layer_desc_t *d) { return use_mfma(d) && d->kind != RMM_SKETCH_SORS; }
 size_t ws_sketch(const rmm_layer_desc_t *d) {
-    return use_mfma(d) ? round_up(sketch_workspace_bf16(d->n, d->d_in, d->k), 256) : 0;
+    return sliced_sketch(d) ? round_up(sketch_workspace_bf16(d->n, d->d_in, d->k), 256) : 0;
 }
 size_t ws_forward(const rmm_layer_desc_t *d) {
-    return use_mfma(d) ? round_up(sketch_workspace_bf16(d->n, d->d_in, d->k, d->d_out), 256) : 0;
+    return sliced_sketch(d) ? round_up(sketch_workspace_bf16(d->n, d->d_in, d->k, d->d_out), 256) : 0;
 }
 size_t ws_backward(const rmm_layer_desc_t *d) {
-    return g_bytes(d) + (use_mfma(d) ? round_up(sketch_workspace_bf16(d->n, d->d_out, d->k, d->d_in), 256) : 0);
+    return g_bytes(d) + (sliced_sketch(d) ? round_up(sketch_workspace_bf16(d->n, d->d_out, d->k, d->d_in), 256) : 0);
 }
 
 // variance monitors: per-block partials (doubles), then, off the MFMA path, X^T dY in fp32.
@@ -122,7 +124,11 @@ int sketch_impl(int64_t n, int64_t d, int64_t k, int kind, SketchState st, const
                 void *ws, hipStream_t stream, const StageEvents &ev = StageEvents(), int product_stage = RMM_STAGE_NONE,
                 int64_t d_other = 0) {
     const bool timed = product_stage != RMM_STAGE_NONE && ev.stage == product_stage;
-    if (mfma)
+    if (kind == RMM_SKETCH_SORS && mfma && sors_fast_ok(n, d)) {  // fast transform; otherwise S is applied densely below
+        StageScope scope(ev, product_stage, stream);
+        return from_hip(launch_sors_bf16((const bf16_t *)A, (bf16_t *)out, n, d, k, st, stream));
+    }
+    if (mfma && kind != RMM_SKETCH_SORS)
         return from_hip(launch_sketch_bf16((const bf16_t *)A, (bf16_t *)out, n, d, k, kind, st, ws, stream,
                                            timed ? ev.begin : nullptr, timed ? ev.end : nullptr, d_other));
     StageScope scope(ev, product_stage, stream);  // the plain path is one kernel
@@ -134,7 +140,8 @@ template <typename T>
 int forward_impl(const rmm_layer_desc_t *d, SketchState st, const void *X, const void *W, const void *bias, void *Y,
                  void *X_proj, void *ws, hipStream_t stream, const StageEvents &ev) {
     const bool mfma = use_mfma(d);
-    if (X_proj != nullptr && mfma && !separate_stage(ev.stage) && forward_pair_available(d->n, d->d_in, d->d_out, d->k)) {
+    if (X_proj != nullptr && sliced_sketch(d) && !separate_stage(ev.stage) &&
+        forward_pair_available(d->n, d->d_in, d->d_out, d->k)) {
         const bool timed = ev.stage == RMM_STAGE_FWD_PAIR;
         return from_hip(launch_forward_pair_bf16((const bf16_t *)X, (const bf16_t *)W, (const bf16_t *)bias, (bf16_t *)Y,
                                                  (bf16_t *)X_proj, d->n, d->d_in, d->d_out, d->k, d->kind, st, ws, stream,
@@ -162,7 +169,7 @@ int backward_impl(const rmm_layer_desc_t *d, SketchState st, const void *dY, con
     hipError_t e;
     const bool mfma = use_mfma(d);
     T *G = (T *)ws;  // G = S^T dY, k x d_out
-    const bool paired = mfma && dX != nullptr && !separate_stage(ev.stage) &&
+    const bool paired = sliced_sketch(d) && dX != nullptr && !separate_stage(ev.stage) &&
                         backward_pair_available(d->n, d->d_in, d->d_out, d->k);
     if (paired) {
         const bool timed = ev.stage == RMM_STAGE_BWD_PAIR;
@@ -234,7 +241,7 @@ size_t rmm_workspace_bytes(const rmm_layer_desc_t *desc, int op) {
 }
 
 int rmm_uses_paired_launch(const rmm_layer_desc_t *desc, int op) {
-    if (!desc_ok(desc) || !use_mfma(desc)) return 0;
+    if (!desc_ok(desc) || !sliced_sketch(desc)) return 0;
     if (op == RMM_OP_FORWARD) return forward_pair_available(desc->n, desc->d_in, desc->d_out, desc->k) ? 1 : 0;
     if (op == RMM_OP_BACKWARD) return backward_pair_available(desc->n, desc->d_in, desc->d_out, desc->k) ? 1 : 0;
     return 0;
@@ -248,7 +255,7 @@ int rmm_sketch_profiled(int64_t n, int64_t d, int64_t k, int dtype, int kind, rm
     if (!grid_ok(k)) return RMM_ERR_UNSUPPORTED;
     const size_t need = ws_sketch(&desc);
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return RMM_ERR_WORKSPACE;
-    const SketchState st = make_state(state.seed, state.offset);
+    const SketchState st = make_state(state.seed, state.offset, n);
     hipStream_t s = (hipStream_t)stream;
     const bool mfma = use_mfma(&desc);
     StageEvents ev;
@@ -278,7 +285,7 @@ int rmm_sketch_static(int64_t n, int64_t d, int64_t k, int dtype, int kind, rmm_
         const int rc = static_scratch_ptr(&ws);
         if (rc != RMM_OK) return rc;
     }
-    const SketchState st = make_state(state.seed, state.offset);
+    const SketchState st = make_state(state.seed, state.offset, n);
     hipStream_t s = (hipStream_t)stream;
     return dtype == RMM_DTYPE_BF16 ? sketch_impl<bf16_t>(n, d, k, kind, st, A, A_proj, use_mfma(&desc), ws, s)
                                    : sketch_impl<float>(n, d, k, kind, st, A, A_proj, false, ws, s);
@@ -293,7 +300,7 @@ int rmm_forward_profiled(const rmm_layer_desc_t *desc, rmm_rng_state_t state, co
     if (!grid_ok(desc->n) || !grid_ok(desc->k)) return RMM_ERR_UNSUPPORTED;
     const size_t need = X_proj != nullptr ? ws_forward(desc) : 0;
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return RMM_ERR_WORKSPACE;
-    const SketchState st = make_state(state.seed, state.offset);
+    const SketchState st = make_state(state.seed, state.offset, desc->n);
     hipStream_t s = (hipStream_t)stream;
     StageEvents ev;
     ev.stage = stage;
@@ -320,7 +327,7 @@ static int backward_checked(const rmm_layer_desc_t *desc, rmm_rng_state_t state,
     if (!grid_ok(desc->n) || !grid_ok(desc->k) || !grid_ok(desc->d_out)) return RMM_ERR_UNSUPPORTED;
     const size_t need = ws_backward(desc);
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return RMM_ERR_WORKSPACE;
-    const SketchState st = make_state(state.seed, state.offset);
+    const SketchState st = make_state(state.seed, state.offset, desc->n);
     hipStream_t s = (hipStream_t)stream;
     StageEvents ev;
     ev.stage = stage;
@@ -356,6 +363,7 @@ int rmm_variance_stats(const rmm_layer_desc_t *desc, const void *X, const void *
     if (!desc_ok(desc) || X == nullptr || dY == nullptr || out == nullptr) return RMM_ERR_INVALID_ARG;
     if (!aligned16(X) || !aligned16(dY) || !aligned16(ws) || ((uintptr_t)out & 7u) != 0) return RMM_ERR_INVALID_ARG;
     if (!use_mfma(desc) && !grid_ok(desc->d_in)) return RMM_ERR_UNSUPPORTED;  // plain X^T dY: d_in rows of tiles
+    if (desc->kind == RMM_SKETCH_SORS) return RMM_ERR_UNSUPPORTED;  // Lemma 2.2 is about i.i.d. entries
     if (ws == nullptr || ws_bytes < ws_variance(desc)) return RMM_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     const int nb = row_norm_blocks(desc->n), nt = var_xty_partials(desc);

@@ -86,6 +86,13 @@ hipError_t launch_backward_pair_bf16(const bf16_t *dY, const bf16_t *W, bf16_t *
                                      int64_t d_out, int64_t k, int kind, SketchState st, void *ws, hipStream_t stream,
                                      hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
 
+// SORS sketch kind, bf16 (sors.hip): signs, Walsh-Hadamard transform along the tokens and row
+// selection in one kernel, no workspace.  Usable when sors_fast_ok(): d a multiple of 8 and at most
+// 32768 tokens (the strip of one work-group has to fit in LDS); `st` made with the token count.
+bool sors_fast_ok(int64_t n, int64_t d);
+hipError_t launch_sors_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d, int64_t k, SketchState st,
+                            hipStream_t stream);
+
 // Variance monitors (variance.hip, and the squared-norm epilogue of the MFMA kernel).
 //   part[3*b..] = per-block (sum |x_k|^2, sum |y_k|^2, sum |x_k|^2 |y_k|^2); row_norm_blocks(n) blocks.
 int row_norm_blocks(int64_t n);

@@ -12,16 +12,25 @@ namespace rmm {
 struct SketchState {
     uint32_t key0, key1;  // seed lo / hi
     uint32_t off0, off1;  // offset lo / hi  (counter words 2 and 3)
+    uint32_t row_mask;    // SORS kind only: n_pad - 1, n_pad = the token count rounded up to a power of two
 };
 
-__host__ __device__ inline SketchState make_state(uint64_t seed, uint64_t offset) {
+// `n` = the sketch's token count; it enters the SORS kind only (through n_pad).
+__host__ __device__ inline SketchState make_state(uint64_t seed, uint64_t offset, int64_t n = 1) {
     SketchState s;
     s.key0 = (uint32_t)seed;
     s.key1 = (uint32_t)(seed >> 32);
     s.off0 = (uint32_t)offset;
     s.off1 = (uint32_t)(offset >> 32);
+    uint32_t n_pad = 1;
+    while ((int64_t)n_pad < n && n_pad < 0x80000000u) n_pad <<= 1;
+    s.row_mask = n_pad - 1u;
     return s;
 }
+
+// Counter word 1 (the slot of the sketch column) of the calls behind the SORS kind's token signs
+// and selected rows; no sketch has that many columns.
+constexpr uint32_t kSorsSignColumn = 0xFFFFFFFFu, kSorsRowColumn = 0xFFFFFFFEu;
 
 struct Words4 {
     uint32_t w[4];
@@ -73,6 +82,14 @@ __device__ __forceinline__ float sketch_entry_precise(int kind, const SketchStat
         float zc, zs;
         gauss_pair_precise(r.w[(i & 7) >> 1], zc, zs);
         return (i & 1) ? zs : zc;
+    }
+    if (kind == 2) {  // SORS: sign of token i times entry (r_j, i) of the Walsh-Hadamard matrix
+        const Words4 rs = philox4x32_10((uint32_t)(i >> 7), kSorsSignColumn, st.off0, st.off1, st.key0, st.key1);
+        const Words4 rr = philox4x32_10((uint32_t)(j >> 2), kSorsRowColumn, st.off0, st.off1, st.key0, st.key1);
+        const uint32_t t = (uint32_t)(i & 127);
+        const uint32_t row = rr.w[j & 3] & st.row_mask;
+        const uint32_t bit = ((rs.w[t >> 5] >> (t & 31)) ^ (uint32_t)__popc(row & (uint32_t)i)) & 1u;
+        return bit ? -1.0f : 1.0f;
     }
     const Words4 r = philox4x32_10((uint32_t)(i >> 7), (uint32_t)j, st.off0, st.off1, st.key0, st.key1);
     const uint32_t t = (uint32_t)(i & 127);

@@ -1,0 +1,122 @@
+"""GPU parity of the SORS sketch kind (signs, Walsh-Hadamard transform along the tokens, row
+selection; the construction is stated in include/rmm.h and oracle/sketch.py and is this build's
+own, so parity with the paper is unpinned): every entry of S read back through an identity
+operand, the sketch primitive and the whole layer against the fp64 oracle, on the fast-transform
+kernel (bf16, width a multiple of 8, at most 32768 tokens) and on the entry-by-entry path that
+serves everything else, and unbiasedness of the weight gradient over many states."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2201_13195_amd as rmm
+from paper_2201_13195_amd import binding, synth
+from oracle import rmm as o_rmm
+from oracle import sketch as o_sketch
+from parity import assert_close
+from test_gpu_parity import check_layer
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+SORS = rmm.SORS
+
+
+@pytest.mark.parametrize("n,k", [(256, 40), (300, 64), (1000, 130), (1024, 1024), (4096, 410), (2056, 77), (8, 5), (1, 3)])
+def test_every_entry_through_an_identity_operand(n, k):
+    """S^T I = S^T: rmm_sketch on an identity returns sigma_i * (-1)^popcount(i AND r_j) / sqrt(k)
+    rounded to bf16: signs exact, magnitude within one rounding.  Token counts on both sides of
+    powers of two (the transform runs on n_pad) and below the kernel's shortest transform."""
+    seed, offset = 0x5EED0020, (1 << 32) | 3
+    d = (n + 7) // 8 * 8
+    A = torch.zeros((n, d), dtype=torch.bfloat16, device=DEV)
+    A[torch.arange(n), torch.arange(n)] = 1.0
+    got = synth.to_f64(rmm.rmm_sketch(A, k, SORS, seed, offset))          # k x d
+    want = o_sketch.sketch_S(n, k, o_sketch.SORS, seed, offset).T        # k x n
+    assert np.array_equal(got[:, n:], np.zeros((k, d - n)))
+    got = got[:, :n]
+    assert np.array_equal(np.signbit(got), np.signbit(want))
+    assert np.abs(np.abs(got) * math.sqrt(k) - 1.0).max() <= 2.0 ** -8
+
+
+@pytest.mark.parametrize("n,d,k", [(256, 64, 32), (700, 264, 33), (4096, 768, 410), (4096, 3072, 410), (5000, 128, 300),
+                                   (16384, 1024, 1638), (32768, 64, 100), (20000, 72, 9)])
+def test_sketch_primitive_fast_transform(n, d, k):
+    A = synth.to_torch(synth.normal((n, d), 0x5EED0021 + n), "bf16")
+    got = rmm.rmm_sketch(A.to(DEV), k, SORS, 0x5EED0022, 5)
+    torch.cuda.synchronize()
+    want = o_rmm.sketch_apply(synth.to_f64(A), k, o_sketch.SORS, 0x5EED0022, 5)
+    err = assert_close(got, want, "X_proj", "bf16", "sors sketch n=%d d=%d k=%d" % (n, d, k))
+    print("sors sketch n=%d d=%d k=%d: %.2e" % (n, d, k, err), flush=True)
+    assert rmm.rmm_workspace_bytes(n, d, d, k, torch.bfloat16, SORS, binding.OP_SKETCH) == 0
+
+
+@pytest.mark.parametrize("dtype,n,d,k", [("f32", 256, 128, 32), ("f32", 333, 50, 77), ("bf16", 333, 52, 20),
+                                         ("bf16", 40000, 8, 8)])
+def test_sketch_primitive_entry_by_entry_path(dtype, n, d, k):
+    """fp32, widths that are not multiples of 8 and more than 32768 tokens: the same S applied densely."""
+    A = synth.to_torch(synth.normal((n, d), 77), dtype)
+    got = rmm.rmm_sketch(A.to(DEV), k, SORS, 0x5EED0023, 6)
+    torch.cuda.synchronize()
+    want = o_rmm.sketch_apply(synth.to_f64(A), k, o_sketch.SORS, 0x5EED0023, 6)
+    assert_close(got, want, "X_proj", dtype, "sors dense %s n=%d d=%d k=%d" % (dtype, n, d, k))
+
+
+@pytest.mark.parametrize("dtype,shape", [("f32", (256, 128, 128, 32)), ("bf16", (333, 200, 136, 77)),
+                                         ("bf16", (1000, 264, 520, 129)), ("bf16", (130, 72, 264, 300))])
+def test_layer_small_and_ragged(dtype, shape):
+    n, d_in, d_out, k = shape
+    X, W, dY = synth.layer_inputs(n, d_in, d_out, dtype, (811, 812, 813))
+    bias = synth.to_torch(synth.normal((d_out,), 814), dtype)
+    check_layer(X, W, dY, k, SORS, 0xABCDEF, 43, dtype, bias=bias, label="sors %s %s" % (shape, dtype))
+
+
+@pytest.mark.parametrize("name", ["c2_base_attn", "c3_base_ffn_up", "c3_base_ffn_down", "c4_large_ffn_up"])
+def test_layer_at_the_paper_shapes(name):
+    c = synth.CONFIGS[name]
+    X, W, dY = synth.layer_inputs(c["n"], c["d_in"], c["d_out"], c["dtype"], c["seeds"])
+    check_layer(X, W, dY, c["k"], SORS, c["seed"], 21, "bf16", label="sors %s" % name)
+    assert not rmm.rmm_uses_paired_launch(c["n"], c["d_in"], c["d_out"], c["k"], torch.bfloat16, SORS, binding.OP_FORWARD)
+
+
+def test_forward_backward_and_sketch_agree_and_are_deterministic():
+    X, W, dY = synth.layer_inputs(1500, 264, 520, "bf16", (31, 32, 33))
+    Xd, Wd, dYd = X.to(DEV), W.to(DEV), dY.to(DEV)
+    Y1, Xp1 = rmm.rmm_forward(Xd, Wd, None, 96, SORS, 5, 6)
+    Y2, Xp2 = rmm.rmm_forward(Xd, Wd, None, 96, SORS, 5, 6)
+    Xp3 = rmm.rmm_sketch(Xd, 96, SORS, 5, 6)
+    assert torch.equal(Y1, Y2) and torch.equal(Xp1, Xp2) and torch.equal(Xp1, Xp3)
+    d1 = rmm.rmm_backward(dYd, Wd, Xp1, SORS, 5, 6)
+    d2 = rmm.rmm_backward(dYd, Wd, Xp1, SORS, 5, 6)
+    assert torch.equal(d1[0], d2[0]) and torch.equal(d1[1], d2[1])
+    assert not torch.equal(Xp1, rmm.rmm_sketch(Xd, 96, SORS, 5, 7))
+    assert not torch.equal(Xp1, rmm.rmm_sketch(Xd, 96, SORS, 4, 6))
+    assert not torch.equal(Xp1, rmm.rmm_sketch(Xd, 96, rmm.RADEMACHER, 5, 6))
+
+
+def test_weight_gradient_is_unbiased_on_the_device():
+    """Mean of dW over 600 states against dY^T X (Eq. 3), at the 1/sqrt(states) rate."""
+    n, d_in, d_out, k, states = 512, 64, 72, 64, 600
+    X, W, dY = synth.layer_inputs(n, d_in, d_out, "bf16", (41, 42, 43))
+    Xd, Wd, dYd = X.to(DEV), W.to(DEV), dY.to(DEV)
+    exact = synth.to_f64(dY).T @ synth.to_f64(X)
+    acc = np.zeros_like(exact)
+    sq = np.zeros_like(exact)
+    for t in range(states):
+        _, Xp = rmm.rmm_forward(Xd, Wd, None, k, SORS, 77, t)
+        _, dW, _ = rmm.rmm_backward(dYd, Wd, Xp, SORS, 77, t, need_dX=False)
+        est = synth.to_f64(dW)
+        acc += est
+        sq += est * est
+    mean = acc / states
+    sd = np.sqrt(np.maximum(sq / states - mean * mean, 0.0) / states)
+    z = np.abs(mean - exact) / (sd + 1e-3 * np.abs(exact).max())
+    assert z.max() < 5.5, z.max()
+    # and the estimator is not trivially exact: one state is far from the mean
+    assert np.linalg.norm(est - exact) > 0.05 * np.linalg.norm(exact)
+
+
+def test_variance_monitor_refuses_the_kind():
+    X, W, dY = synth.layer_inputs(256, 128, 128, "bf16", (1, 2, 3))
+    with pytest.raises(rmm.RmmError):
+        rmm.rmm_variance_stats(X.to(DEV), dY.to(DEV), 32, SORS)
