@@ -316,6 +316,24 @@ def layer_report(run, cfg, kind_name, steps, peaks):
             "kernels": kernels}
 
 
+def sors_report(run, cfg, steps, dense_ms):
+    """The structured sketch kind (SORS: signs, Walsh-Hadamard transform along the tokens, row
+    selection) on the same layer: step time, and its two sketch stages against the HBM roofline
+    (algorithmic bytes = one read of the operand + one write of the k selected rows)."""
+    n, d_in, d_out, k = cfg["n"], cfg["d_in"], cfg["d_out"], cfg["k"]
+    ms = run.step_ms(steps)
+    stage_ms, kernel_ms, _ = run.stage_table(reps=5)
+    stages = {}
+    for name, d in (("fwd_Xproj", d_in), ("bwd_G", d_out)):
+        nbytes = 2 * (n * d + k * d)
+        gbs = nbytes / (kernel_ms[name] * 1e-3) / 1e9
+        stages[name] = {"ms": kernel_ms[name], "algorithmic_bytes": nbytes, "bound": "hbm", "achieved": gbs,
+                        "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}
+    return {"workload": "N=%d tokens, d_in=%d, d_out=%d, k=%d (SORS sketch), bf16" % (n, d_in, d_out, k),
+            "ms_per_step": ms, "steps": steps, "stages_ms": stage_ms, "sketch_stages": stages,
+            "step_time_vs_dense_sketch": ms / dense_ms if dense_ms else None}
+
+
 def measured_peaks(torch, rmm, dev, reps=5):
     """What a kernel that only issues MFMAs, and one that only reads memory, reach on this machine
     (rmm_probe_mfma on one work-group per compute unit; rmm_probe_read over three rotating 512 MiB
@@ -357,7 +375,7 @@ def measured_peaks(torch, rmm, dev, reps=5):
     read()
     hbm = timed(read) / 1e9
     return {"mfma_bf16_tflops": mfma, "mfma_bf16_tflops_sustained": mfma_sustained, "hbm_read_gbs": hbm, "compute_units": cus,
-            "how": "best of %d launches: 32x32x16 bf16 MFMAs from registers on one 4-wave work-group per compute unit; "
+            "how": "best of %d launches: 32x32x16 bf16 MFMAs on pseudo-random operands held in registers, one 4-wave work-group per compute unit; "
                    "sustained = launches 31-60 of 60 back to back (about 0.13 s); "
                    "one streaming read of 512 MiB (three buffers in turn)" % reps}
 
@@ -498,6 +516,12 @@ def main():
         out["other_kind"] = layer_report(LayerRun(torch, rmm, binding, synth, dev, cfg, other, args.sets), cfg,
                                          "rademacher" if other == rmm.RADEMACHER else "gaussian", 50,
                                          out.get("measured_peaks"))
+        # the structured sketch kind on both shapes (dense sketch of the main line for comparison)
+        out["sors_kind"] = {
+            "headline_shape": sors_report(LayerRun(torch, rmm, binding, synth, dev, cfg, rmm.SORS, args.sets), cfg, 50,
+                                          ms_per_step),
+            "large_shape": sors_report(LayerRun(torch, rmm, binding, synth, dev, big, rmm.SORS, 2), big, 20,
+                                       out["large_shape"]["ms_per_step"])}
     if not args.no_sketch_roofline:
         out["sketch_hbm_roofline"] = sk = sketch_roofline(torch, rmm, binding, dev, kind, args.kind, version)
         if "measured_peaks" in out:

@@ -20,9 +20,17 @@ __global__ void __launch_bounds__(256) probe_mfma_kernel(float *sink, int iters)
     for (int a = 0; a < 16; ++a)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[a][v] = 0.0f;
+    // Operands with pseudo-random signs and mantissas (magnitudes in [0.5, 1)): constant operands
+    // toggle few bits in the multipliers and draw less power than a real product does.
     bf16x8_t fa, fb;
+    uint32_t h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) fa[i] = (__bf16)(1.0f + (float)(threadIdx.x & 3)), fb[i] = (__bf16)(0.5f);
+    for (int i = 0; i < 8; ++i) {
+        h = h * 1664525u + 1013904223u;
+        fa[i] = (__bf16)__uint_as_float(0x3F000000u | (h & 0x80000000u) | ((h >> 1) & 0x007F0000u));
+        h = h * 1664525u + 1013904223u;
+        fb[i] = (__bf16)__uint_as_float(0x3F000000u | (h & 0x80000000u) | ((h >> 1) & 0x007F0000u));
+    }
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int a = 0; a < 16; ++a) acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[a], 0, 0, 0);
