@@ -522,6 +522,14 @@ def main():
                                           ms_per_step),
             "large_shape": sors_report(LayerRun(torch, rmm, binding, synth, dev, big, rmm.SORS, 2), big, 20,
                                        out["large_shape"]["ms_per_step"])}
+        # the fp32 data path (plain FMA kernels, full-precision generator) on the headline shape
+        f32 = dict(cfg, dtype="f32")
+        run32 = LayerRun(torch, rmm, binding, synth, dev, f32, kind, 2)
+        ms32 = run32.step_ms(5)
+        out["fp32_path"] = {"workload": "N=%d tokens, d_in=%d, d_out=%d, k=%d (%s sketch), f32" % (n, d_in, d_out, k, args.kind),
+                            "ms_per_step": ms32, "tflops": total_flops / (ms32 * 1e-3) / 1e12, "bound": "alu",
+                            "peak": PEAK_F32_TFLOPS, "frac": total_flops / (ms32 * 1e-3) / 1e12 / PEAK_F32_TFLOPS, "steps": 5}
+        del run32
     if not args.no_sketch_roofline:
         out["sketch_hbm_roofline"] = sk = sketch_roofline(torch, rmm, binding, dev, kind, args.kind, version)
         if "measured_peaks" in out:

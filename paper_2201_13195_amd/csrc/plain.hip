@@ -28,6 +28,64 @@ struct SketchSrc {
     __device__ float at(int64_t j, int64_t i) const { return sketch_entry_precise(kind, st, i, j); }
 };
 
+// The TM x TK tile of an operand (rows m0 .., contraction k0 .., k0 a multiple of TK) into LDS,
+// zeros beyond the operand.
+template <typename T>
+__device__ __forceinline__ void fill_a_tile(const MemSrc<T> &A, float (&As)[TK][TM + 4], int64_t m0, int64_t k0, int64_t m,
+                                            int64_t kk, int tid) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int e = tid + 256 * q, kl = e & 15, rl = e >> 4;
+        As[kl][rl] = (m0 + rl < m && k0 + kl < kk) ? A.at(m0 + rl, k0 + kl) : 0.0f;
+    }
+}
+// The same for P^T, with one Philox call serving all the entries it covers in the tile instead of
+// one call per entry: a Gaussian call covers 8 consecutive tokens of a column (two calls per
+// column and tile), a Rademacher call 128 (the tile's 16 tokens lie inside one call), and the
+// SORS kind needs the tile's sign words once and one row number per column.  Values are those of
+// sketch_entry_precise.
+__device__ __forceinline__ void fill_a_tile(const SketchSrc &A, float (&As)[TK][TM + 4], int64_t m0, int64_t k0, int64_t m,
+                                            int64_t kk, int tid) {
+    static_assert(TK == 16 && TM == 64, "two 8-token groups per column, 64 columns");
+    const SketchState &st = A.st;
+    if (A.kind == 0) {
+        if (tid < 2 * TM) {
+            const int col = tid >> 1, grp = tid & 1;
+            const int64_t j = m0 + col, t0 = k0 + 8 * grp;
+            const Words4 r = philox4x32_10((uint32_t)(t0 >> 3), (uint32_t)j, st.off0, st.off1, st.key0, st.key1);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float zc, zs;
+                gauss_pair_precise(r.w[q], zc, zs);
+                As[8 * grp + 2 * q][col] = (j < m && t0 + 2 * q < kk) ? zc : 0.0f;
+                As[8 * grp + 2 * q + 1][col] = (j < m && t0 + 2 * q + 1 < kk) ? zs : 0.0f;
+            }
+        }
+        return;
+    }
+    if (tid < TM) {
+        const int col = tid;
+        const int64_t j = m0 + col;
+        const uint32_t t = (uint32_t)(k0 & 127), word = t >> 5, shift = t & 31;  // the 16 tokens share one word
+        uint32_t bits, row = 0;
+        if (A.kind == 1) {
+            const Words4 r = philox4x32_10((uint32_t)(k0 >> 7), (uint32_t)j, st.off0, st.off1, st.key0, st.key1);
+            bits = (word == 0 ? r.w[0] : word == 1 ? r.w[1] : word == 2 ? r.w[2] : r.w[3]) >> shift;
+        } else {
+            const Words4 rs = philox4x32_10((uint32_t)(k0 >> 7), kSorsSignColumn, st.off0, st.off1, st.key0, st.key1);
+            const Words4 rr = philox4x32_10((uint32_t)(j >> 2), kSorsRowColumn, st.off0, st.off1, st.key0, st.key1);
+            const uint32_t q = (uint32_t)(j & 3);
+            bits = (word == 0 ? rs.w[0] : word == 1 ? rs.w[1] : word == 2 ? rs.w[2] : rs.w[3]) >> shift;
+            row = (q == 0 ? rr.w[0] : q == 1 ? rr.w[1] : q == 2 ? rr.w[2] : rr.w[3]) & st.row_mask;
+        }
+#pragma unroll
+        for (int i = 0; i < TK; ++i) {
+            const uint32_t neg = ((bits >> i) ^ (uint32_t)__popc(row & (uint32_t)(k0 + i))) & 1u;
+            As[i][col] = (j < m && k0 + i < kk) ? (neg ? -1.0f : 1.0f) : 0.0f;
+        }
+    }
+}
+
 // C[m x n] = alpha * A[m x kk] * B[kk x n] (+ bias).  A.at(row, kk), B.at(kk, col).
 template <typename ASrc, typename BSrc, typename Tout, typename Tbias>
 __global__ void __launch_bounds__(256) gemm_plain_kernel(ASrc A, BSrc B, Tout *__restrict__ C, int64_t ldc,
@@ -40,14 +98,12 @@ __global__ void __launch_bounds__(256) gemm_plain_kernel(ASrc A, BSrc B, Tout *_
     const int64_t m0 = (int64_t)blockIdx.y * TM, n0 = (int64_t)blockIdx.x * TN;
     float acc[4][4] = {};
     for (int64_t k0 = 0; k0 < kk; k0 += TK) {
+        fill_a_tile(A, As, m0, k0, m, kk, tid);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int e = tid + 256 * q;  // 0..1023
             const int kl = e & 15, rl = e >> 4;
-            const int64_t gk = k0 + kl;
-            const int64_t gm = m0 + rl, gn = n0 + rl;
-            As[kl][rl] = (gm < m && gk < kk) ? A.at(gm, gk) : 0.0f;
-            Bs[kl][rl] = (gn < n && gk < kk) ? B.at(gk, gn) : 0.0f;
+            Bs[kl][rl] = (n0 + rl < n && k0 + kl < kk) ? B.at(k0 + kl, n0 + rl) : 0.0f;
         }
         __syncthreads();
 #pragma unroll

@@ -130,3 +130,25 @@ def test_default_layers_draw_independent_sketches_and_no_grad_skips_the_sketch()
     with torch.no_grad():
         Y0 = a(X.to(DEV))
     assert a.calls == calls and torch.equal(Y0, Ya.detach())
+
+
+def test_layer_with_the_sors_kind_matches_the_oracle():
+    """nn.Linear form with kind = SORS: forward value, input gradient (exact) and weight gradient
+    (the estimate for the state the layer used) against the fp64 oracle."""
+    from oracle import rmm as o_rmm
+    from oracle import sketch as o_sketch
+    from parity import assert_close
+    n, d_in, d_out, k = 1000, 264, 136, 200
+    X, W, dY = synth.layer_inputs(n, d_in, d_out, "bf16", (94, 95, 96))
+    layer = rmm.RMMLinear(d_in, d_out, bias=False, k=k, kind=rmm.SORS)
+    with torch.no_grad():
+        layer.weight.copy_(W.to(DEV))
+    Xd = X.to(DEV).requires_grad_(True)
+    Y = layer(Xd)
+    Y.backward(dY.to(DEV))
+    seed, offset = layer.last_state
+    oY, oXp = o_rmm.forward(synth.to_f64(X), synth.to_f64(W), None, k, o_sketch.SORS, seed, offset)
+    odX, odW, _ = o_rmm.backward(synth.to_f64(dY), synth.to_f64(W), oXp, o_sketch.SORS, seed, offset)
+    assert_close(Y.detach(), oY, "Y", "bf16", "sors layer")
+    assert_close(Xd.grad, odX, "dX", "bf16", "sors layer")
+    assert_close(layer.weight.grad, odW, "dW", "bf16", "sors layer")

@@ -47,3 +47,7 @@ def test_static_scratch_limit_is_an_error_code():
     A = synth.to_torch(synth.normal((300, 40), 64), "f32").to(DEV)
     out = torch.empty((9, 40), dtype=torch.float32, device=DEV)
     assert torch.equal(rmm.rmm_sketch_static(A, 9, 0, 3, 4, out), rmm.rmm_sketch(A, 9, 0, 3, 4))
+    # the SORS kind needs no scratch either (its sketch product is one kernel without partial sums)
+    B = synth.to_torch(synth.normal((5000, 264), 65), "bf16").to(DEV)
+    out = torch.empty((130, 264), dtype=torch.bfloat16, device=DEV)
+    assert torch.equal(rmm.rmm_sketch_static(B, 130, rmm.SORS, 3, 4, out), rmm.rmm_sketch(B, 130, rmm.SORS, 3, 4))
