@@ -322,7 +322,7 @@ def sors_report(run, cfg, steps, dense_ms):
     (algorithmic bytes = one read of the operand + one write of the k selected rows)."""
     n, d_in, d_out, k = cfg["n"], cfg["d_in"], cfg["d_out"], cfg["k"]
     ms = run.step_ms(steps)
-    stage_ms, kernel_ms, _ = run.stage_table(reps=5)
+    stage_ms, kernel_ms, pair_ms = run.stage_table(reps=5)
     stages = {}
     for name, d in (("fwd_Xproj", d_in), ("bwd_G", d_out)):
         nbytes = 2 * (n * d + k * d)
@@ -330,7 +330,7 @@ def sors_report(run, cfg, steps, dense_ms):
         stages[name] = {"ms": kernel_ms[name], "algorithmic_bytes": nbytes, "bound": "hbm", "achieved": gbs,
                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}
     return {"workload": "N=%d tokens, d_in=%d, d_out=%d, k=%d (SORS sketch), bf16" % (n, d_in, d_out, k),
-            "ms_per_step": ms, "steps": steps, "stages_ms": stage_ms, "sketch_stages": stages,
+            "ms_per_step": ms, "steps": steps, "stages_ms": stage_ms, "paired_kernel_ms": pair_ms, "sketch_stages": stages,
             "step_time_vs_dense_sketch": ms / dense_ms if dense_ms else None}
 
 

@@ -147,6 +147,13 @@ int forward_impl(const rmm_layer_desc_t *d, SketchState st, const void *X, const
                                                  (bf16_t *)X_proj, d->n, d->d_in, d->d_out, d->k, d->kind, st, ws, stream,
                                                  timed ? ev.begin : nullptr, timed ? ev.end : nullptr));
     }
+    if (X_proj != nullptr && mfma && d->kind == RMM_SKETCH_SORS && !separate_stage(ev.stage) &&
+        sors_pair_available(d->n, d->d_in, d->d_out, d->k)) {
+        const bool timed = ev.stage == RMM_STAGE_FWD_PAIR;
+        return from_hip(launch_forward_pair_sors_bf16((const bf16_t *)X, (const bf16_t *)W, (const bf16_t *)bias, (bf16_t *)Y,
+                                                      (bf16_t *)X_proj, d->n, d->d_in, d->d_out, d->k, st, stream,
+                                                      timed ? ev.begin : nullptr, timed ? ev.end : nullptr));
+    }
     {   // Y = X W^T (+ bias): A = X (n x d_in), B(kk, c) = W[c][kk].
         StageScope scope(ev, RMM_STAGE_FWD_Y, stream);
         hipError_t e =
@@ -169,9 +176,17 @@ int backward_impl(const rmm_layer_desc_t *d, SketchState st, const void *dY, con
     hipError_t e;
     const bool mfma = use_mfma(d);
     T *G = (T *)ws;  // G = S^T dY, k x d_out
-    const bool paired = sliced_sketch(d) && dX != nullptr && !separate_stage(ev.stage) &&
-                        backward_pair_available(d->n, d->d_in, d->d_out, d->k);
-    if (paired) {
+    const bool paired_sors = mfma && d->kind == RMM_SKETCH_SORS && dX != nullptr && !separate_stage(ev.stage) &&
+                             sors_pair_available(d->n, d->d_out, d->d_in, d->k);
+    if (paired_sors) {
+        const bool timed = ev.stage == RMM_STAGE_BWD_PAIR;
+        e = launch_backward_pair_sors_bf16((const bf16_t *)dY, (const bf16_t *)W, (bf16_t *)dX, (bf16_t *)G, d->n, d->d_in,
+                                           d->d_out, d->k, st, stream, timed ? ev.begin : nullptr, timed ? ev.end : nullptr);
+        if (e != hipSuccess) return RMM_ERR_LAUNCH;
+    }
+    const bool paired = paired_sors || (sliced_sketch(d) && dX != nullptr && !separate_stage(ev.stage) &&
+                                        backward_pair_available(d->n, d->d_in, d->d_out, d->k));
+    if (paired && !paired_sors) {
         const bool timed = ev.stage == RMM_STAGE_BWD_PAIR;
         e = launch_backward_pair_bf16((const bf16_t *)dY, (const bf16_t *)W, (bf16_t *)dX, (bf16_t *)G, d->n, d->d_in,
                                       d->d_out, d->k, d->kind, st, (char *)ws + g_bytes(d), stream,
@@ -241,7 +256,12 @@ size_t rmm_workspace_bytes(const rmm_layer_desc_t *desc, int op) {
 }
 
 int rmm_uses_paired_launch(const rmm_layer_desc_t *desc, int op) {
-    if (!desc_ok(desc) || !sliced_sketch(desc)) return 0;
+    if (!desc_ok(desc) || !use_mfma(desc)) return 0;
+    if (desc->kind == RMM_SKETCH_SORS) {
+        if (op == RMM_OP_FORWARD) return sors_pair_available(desc->n, desc->d_in, desc->d_out, desc->k) ? 1 : 0;
+        if (op == RMM_OP_BACKWARD) return sors_pair_available(desc->n, desc->d_out, desc->d_in, desc->k) ? 1 : 0;
+        return 0;
+    }
     if (op == RMM_OP_FORWARD) return forward_pair_available(desc->n, desc->d_in, desc->d_out, desc->k) ? 1 : 0;
     if (op == RMM_OP_BACKWARD) return backward_pair_available(desc->n, desc->d_in, desc->d_out, desc->k) ? 1 : 0;
     return 0;

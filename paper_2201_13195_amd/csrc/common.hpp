@@ -93,6 +93,17 @@ bool sors_fast_ok(int64_t n, int64_t d);
 hipError_t launch_sors_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d, int64_t k, SketchState st,
                             hipStream_t stream);
 
+// One launch for the plain product of a pass and the SORS sketch product of the same pass, where
+// the plain product leaves compute units idle (mfma.hip decides, mfma_pair_sors.hip holds the
+// kernels).  Same results as the separate launches, bit for bit.
+bool sors_pair_available(int64_t n, int64_t d_sk, int64_t d_other, int64_t k);
+hipError_t launch_forward_pair_sors_bf16(const bf16_t *X, const bf16_t *W, const bf16_t *bias, bf16_t *Y, bf16_t *X_proj,
+                                         int64_t n, int64_t d_in, int64_t d_out, int64_t k, SketchState st,
+                                         hipStream_t stream, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
+hipError_t launch_backward_pair_sors_bf16(const bf16_t *dY, const bf16_t *W, bf16_t *dX, bf16_t *G, int64_t n,
+                                          int64_t d_in, int64_t d_out, int64_t k, SketchState st, hipStream_t stream,
+                                          hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
+
 // Variance monitors (variance.hip, and the squared-norm epilogue of the MFMA kernel).
 //   part[3*b..] = per-block (sum |x_k|^2, sum |y_k|^2, sum |x_k|^2 |y_k|^2); row_norm_blocks(n) blocks.
 int row_norm_blocks(int64_t n);

@@ -1,6 +1,7 @@
 // bf16 MFMA path of the RMM layer: which kernel of mfma_kernels.hpp serves which product at
 // which shape, and the launches.
 #include "mfma_pair.hpp"
+#include "sors_kernels.hpp"
 
 namespace rmm {
 
@@ -345,6 +346,47 @@ hipError_t launch_backward_pair_bf16(const bf16_t *dY, const bf16_t *W, bf16_t *
     pev.done();
     if (e != hipSuccess) return e;
     return launch_reduce(ws, G, k, d_out, p.splits, stream);
+}
+
+// ---- SORS kind: the plain product of a pass together with the strips of its sketch product.
+// Worth it when the plain product leaves at least 32 compute units idle in its last round (the
+// sketch work-groups need a compute unit to themselves); the strip kernel's chunked form must
+// apply (at least 4096 tokens after padding, at most 2048 sketch columns).
+static int sors_chunks(int64_t n) {
+    int l = 0;
+    while (((int64_t)1 << l) < n) ++l;
+    return l >= 12 ? 1 << (l - 11) : 0;
+}
+
+bool sors_pair_available(int64_t n, int64_t d_sk, int64_t d_other, int64_t k) {
+    if (!sors_fast_ok(n, d_sk) || sors_chunks(n) == 0 || k > 2048) return false;
+    const int cfg = gemm_cfg(n, d_other, d_sk);
+    if (!(cfg == GEMM_LARGE || (cfg == GEMM_SPLIT && plain_depth(d_sk, ShapeSplit::BK) == 4))) return false;
+    const int64_t blocks_a = cfg == GEMM_LARGE ? tiles_of(n, d_other, ShapeLarge::BM, ShapeLarge::BN)
+                                               : tiles_of(n, d_other, ShapeSplit::BM, ShapeSplit::BN);
+    return (256 - blocks_a % 256) % 256 >= 32;
+}
+
+static hipError_t launch_pass_sors(const GemmArgs &ga, bool row_indexed_b, const bf16_t *A, bf16_t *out, int64_t n, int64_t d_sk,
+                                   int64_t k, SketchState st, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end) {
+    const int cfg = gemm_cfg(ga.M, ga.N, ga.K);
+    const int blocks_a = (int)(cfg == GEMM_LARGE ? tiles_of(ga.M, ga.N, ShapeLarge::BM, ShapeLarge::BN)
+                                                 : tiles_of(ga.M, ga.N, ShapeSplit::BM, ShapeSplit::BN));
+    const SorsArgs gs{A, out, n, d_sk, k, st, 1.0f / sqrtf((float)k)};
+    EventPair pev(ev_begin, ev_end, stream);
+    return launch_pair_sors(cfg, row_indexed_b, ga, gs, blocks_a, sors_chunks(n), stream);
+}
+
+hipError_t launch_forward_pair_sors_bf16(const bf16_t *X, const bf16_t *W, const bf16_t *bias, bf16_t *Y, bf16_t *X_proj,
+                                         int64_t n, int64_t d_in, int64_t d_out, int64_t k, SketchState st,
+                                         hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end) {
+    return launch_pass_sors(args_nt(X, W, bias, Y, n, d_in, d_out), false, X, X_proj, n, d_in, k, st, stream, ev_begin, ev_end);
+}
+
+hipError_t launch_backward_pair_sors_bf16(const bf16_t *dY, const bf16_t *W, bf16_t *dX, bf16_t *G, int64_t n,
+                                          int64_t d_in, int64_t d_out, int64_t k, SketchState st, hipStream_t stream,
+                                          hipEvent_t ev_begin, hipEvent_t ev_end) {
+    return launch_pass_sors(args_nn(dY, W, dX, n, d_in, d_out), true, dY, G, n, d_out, k, st, stream, ev_begin, ev_end);
 }
 
 }  // namespace rmm

@@ -166,16 +166,21 @@ def test_operands_of_two_gib_or_more_stay_on_the_mfma_path(lib):
 
 
 def test_sors_kind_at_the_boundary(lib):
-    """The structured kind needs no token-slice scratch (its sketch products are one kernel), has
-    no paired launch and no variance monitor; unknown kinds stay invalid."""
+    """The structured kind needs no token-slice scratch (its sketch products are one kernel), shares
+    a launch with the plain product only where that leaves compute units idle, and has no
+    variance monitor; unknown kinds stay invalid."""
     bf = torch.bfloat16
     assert rmm.SORS == 2
     assert rmm.rmm_workspace_bytes(4096, 768, 768, 410, bf, rmm.SORS, binding.OP_SKETCH) == 0
     assert rmm.rmm_workspace_bytes(4096, 768, 3072, 410, bf, rmm.SORS, binding.OP_FORWARD) == 0
     assert rmm.rmm_workspace_bytes(4096, 768, 3072, 410, bf, rmm.SORS, binding.OP_BACKWARD) == 410 * 3072 * 2
     assert rmm.rmm_workspace_bytes(4096, 768, 3072, 410, bf, 3, binding.OP_BACKWARD) == 0
-    assert not rmm.rmm_uses_paired_launch(4096, 768, 3072, 410, bf, rmm.SORS, binding.OP_FORWARD)
-    assert not rmm.rmm_uses_paired_launch(4096, 768, 3072, 410, bf, rmm.SORS, binding.OP_BACKWARD)
+    assert rmm.rmm_uses_paired_launch(4096, 768, 3072, 410, bf, rmm.SORS, binding.OP_FORWARD)       # 192 tiles on 256 CUs
+    assert rmm.rmm_uses_paired_launch(4096, 768, 3072, 410, bf, rmm.SORS, binding.OP_BACKWARD)
+    assert not rmm.rmm_uses_paired_launch(16384, 1024, 4096, 1638, bf, rmm.SORS, binding.OP_FORWARD)  # 1024 tiles: no idle CU
+    assert not rmm.rmm_uses_paired_launch(4096, 768, 768, 410, bf, rmm.SORS, binding.OP_FORWARD)      # 256-thread plain tiles
+    assert not rmm.rmm_uses_paired_launch(2048, 768, 3072, 410, bf, rmm.SORS, binding.OP_FORWARD)     # a single chunk
+    assert not rmm.rmm_uses_paired_launch(4096, 768, 3072, 2049, bf, rmm.SORS, binding.OP_FORWARD)    # too many sketch columns
     assert rmm.rmm_uses_paired_launch(4096, 768, 3072, 410, bf, rmm.GAUSSIAN, binding.OP_BACKWARD)
     D, fake = binding._Desc, ctypes.c_void_p(0x1000)
     lib.rmm_variance_stats.restype = ctypes.c_int

@@ -78,7 +78,6 @@ def test_layer_at_the_paper_shapes(name):
     c = synth.CONFIGS[name]
     X, W, dY = synth.layer_inputs(c["n"], c["d_in"], c["d_out"], c["dtype"], c["seeds"])
     check_layer(X, W, dY, c["k"], SORS, c["seed"], 21, "bf16", label="sors %s" % name)
-    assert not rmm.rmm_uses_paired_launch(c["n"], c["d_in"], c["d_out"], c["k"], torch.bfloat16, SORS, binding.OP_FORWARD)
 
 
 def test_forward_backward_and_sketch_agree_and_are_deterministic():
@@ -122,3 +121,27 @@ def test_variance_monitor_refuses_the_kind():
     X, W, dY = synth.layer_inputs(256, 128, 128, "bf16", (1, 2, 3))
     with pytest.raises(rmm.RmmError):
         rmm.rmm_variance_stats(X.to(DEV), dY.to(DEV), 32, SORS)
+
+
+@pytest.mark.parametrize("name", ["c3_base_ffn_up", "c3_base_ffn_down"])
+def test_paired_launch_gives_the_bits_of_the_separate_launches(name):
+    """Where the plain product of a pass leaves compute units idle, the strips of the sketch
+    product share its launch; asking for a single product's stage makes the pass launch them one
+    after the other.  Same kernels' arithmetic either way: every output must agree bit for bit."""
+    c = synth.CONFIGS[name]
+    n, d_in, d_out, k = c["n"], c["d_in"], c["d_out"], c["k"]
+    assert rmm.rmm_uses_paired_launch(n, d_in, d_out, k, torch.bfloat16, SORS, binding.OP_FORWARD)
+    assert rmm.rmm_uses_paired_launch(n, d_in, d_out, k, torch.bfloat16, SORS, binding.OP_BACKWARD)
+    X, W, dY = synth.layer_inputs(n, d_in, d_out, "bf16", c["seeds"])
+    Xd, Wd, dYd = X.to(DEV), W.to(DEV), dY.to(DEV)
+    Y0, Xp0 = rmm.rmm_forward(Xd, Wd, None, k, SORS, 9, 1)
+    dX0, dW0, _ = rmm.rmm_backward(dYd, Wd, Xp0, SORS, 9, 1)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    Y1, Xp1 = rmm.rmm_forward(Xd, Wd, None, k, SORS, 9, 1, profile=(binding.STAGE_FWD_Y, a, b))
+    dX1, dW1, _ = rmm.rmm_backward(dYd, Wd, Xp1, SORS, 9, 1, profile=(binding.STAGE_BWD_DX, a, b))
+    torch.cuda.synchronize()
+    assert torch.equal(Y0, Y1) and torch.equal(Xp0, Xp1) and torch.equal(dX0, dX1) and torch.equal(dW0, dW1)
+    # a width with an odd number of strips: the last work-group of the pair has one live strip
+    X2, W2, dY2 = synth.layer_inputs(4096, 776, 3080, "bf16", (7, 8, 9))
+    if rmm.rmm_uses_paired_launch(4096, 776, 3080, 300, torch.bfloat16, SORS, binding.OP_FORWARD):
+        check_layer(X2, W2, dY2, 300, SORS, 0xFEED, 3, "bf16", label="sors paired, odd strips")
