@@ -41,6 +41,7 @@ def test_every_entry_through_an_identity_operand(n, k):
 
 @pytest.mark.parametrize("n,d,k", [(256, 64, 32), (700, 264, 33), (4096, 768, 410), (4096, 3072, 410), (5000, 128, 300),
                                    (16384, 1024, 1638), (32768, 64, 100), (20000, 72, 9),
+                                   (2048, 64, 50), (2049, 64, 50), (4097, 64, 50), (8192, 72, 2048),
                                    # more than 2048 sketch columns: one chunk (n <= 4096), whole strips in LDS (n > 4096)
                                    (4096, 64, 3686), (3000, 72, 2049), (9000, 64, 2100), (16384, 16, 2304), (30000, 8, 2050)])
 def test_sketch_primitive_fast_transform(n, d, k):
