@@ -358,13 +358,22 @@ static int sors_chunks(int64_t n) {
     return l >= 12 ? 1 << (l - 11) : 0;
 }
 
+// 0: separate launches; 1: strips behind the plain tiles (they fill the compute units its last
+// round leaves idle, at least 32 of them); 2: strips in front (the plain product runs three or more
+// rounds and the strips, few and long, occupy at most a quarter of the chip beside its first rounds).
+static int sors_pair_order(int64_t blocks_a, int64_t strip_groups) {
+    if ((256 - blocks_a % 256) % 256 >= 32) return 1;
+    if (blocks_a >= 256 && strip_groups <= 64) return 2;
+    return 0;
+}
+
 bool sors_pair_available(int64_t n, int64_t d_sk, int64_t d_other, int64_t k) {
     if (!sors_fast_ok(n, d_sk) || sors_chunks(n) == 0 || k > 2048) return false;
     const int cfg = gemm_cfg(n, d_other, d_sk);
     if (!(cfg == GEMM_LARGE || (cfg == GEMM_SPLIT && plain_depth(d_sk, ShapeSplit::BK) == 4))) return false;
     const int64_t blocks_a = cfg == GEMM_LARGE ? tiles_of(n, d_other, ShapeLarge::BM, ShapeLarge::BN)
                                                : tiles_of(n, d_other, ShapeSplit::BM, ShapeSplit::BN);
-    return (256 - blocks_a % 256) % 256 >= 32;
+    return sors_pair_order(blocks_a, (d_sk / 8 + 1) / 2) != 0;
 }
 
 static hipError_t launch_pass_sors(const GemmArgs &ga, bool row_indexed_b, const bf16_t *A, bf16_t *out, int64_t n, int64_t d_sk,
@@ -374,7 +383,8 @@ static hipError_t launch_pass_sors(const GemmArgs &ga, bool row_indexed_b, const
                                                  : tiles_of(ga.M, ga.N, ShapeSplit::BM, ShapeSplit::BN));
     const SorsArgs gs{A, out, n, d_sk, k, st, 1.0f / sqrtf((float)k)};
     EventPair pev(ev_begin, ev_end, stream);
-    return launch_pair_sors(cfg, row_indexed_b, ga, gs, blocks_a, sors_chunks(n), stream);
+    return launch_pair_sors(cfg, row_indexed_b, ga, gs, blocks_a, sors_chunks(n), sors_pair_order(blocks_a, (d_sk / 8 + 1) / 2) == 2,
+                            stream);
 }
 
 hipError_t launch_forward_pair_sors_bf16(const bf16_t *X, const bf16_t *W, const bf16_t *bias, bf16_t *Y, bf16_t *X_proj,

@@ -28,10 +28,11 @@ hipError_t launch_pair_nn_split(int sk_cfg, int kind, const GemmArgs &ga, const 
 
 // The same for the SORS sketch kind (mfma_pair_sors.hip): `gs` describes the sketch product, whose
 // strips go two to a work-group; cfg_a is GEMM_LARGE (depth 3) or GEMM_SPLIT (depth 4), row_indexed_b
-// says whether the plain product is dX = dY W (true) or Y = X W^T (false); `chunks` chunks of 2048 tokens.
+// says whether the plain product is dX = dY W (true) or Y = X W^T (false); `chunks` chunks of 2048 tokens;
+// sors_first puts the strips' work-groups at the front of the grid instead of the back.
 struct SorsArgs;
 hipError_t launch_pair_sors(int cfg_a, bool row_indexed_b, const GemmArgs &ga, const SorsArgs &gs, int blocks_a, int chunks,
-                            hipStream_t stream);
+                            bool sors_first, hipStream_t stream);
 
 // Shared body of the four functions above.
 template <typename SA, int BMODE_A, int DA>

@@ -177,7 +177,8 @@ def test_sors_kind_at_the_boundary(lib):
     assert rmm.rmm_workspace_bytes(4096, 768, 3072, 410, bf, 3, binding.OP_BACKWARD) == 0
     assert rmm.rmm_uses_paired_launch(4096, 768, 3072, 410, bf, rmm.SORS, binding.OP_FORWARD)       # 192 tiles on 256 CUs
     assert rmm.rmm_uses_paired_launch(4096, 768, 3072, 410, bf, rmm.SORS, binding.OP_BACKWARD)
-    assert not rmm.rmm_uses_paired_launch(16384, 1024, 4096, 1638, bf, rmm.SORS, binding.OP_FORWARD)  # 1024 tiles: no idle CU
+    assert rmm.rmm_uses_paired_launch(16384, 1024, 4096, 1638, bf, rmm.SORS, binding.OP_FORWARD)      # few long strips beside 4 rounds of tiles
+    assert not rmm.rmm_uses_paired_launch(16384, 1024, 4096, 1638, bf, rmm.SORS, binding.OP_BACKWARD) # as many strip groups as CUs
     assert not rmm.rmm_uses_paired_launch(4096, 768, 768, 410, bf, rmm.SORS, binding.OP_FORWARD)      # 256-thread plain tiles
     assert not rmm.rmm_uses_paired_launch(2048, 768, 3072, 410, bf, rmm.SORS, binding.OP_FORWARD)     # a single chunk
     assert not rmm.rmm_uses_paired_launch(4096, 768, 3072, 2049, bf, rmm.SORS, binding.OP_FORWARD)    # too many sketch columns

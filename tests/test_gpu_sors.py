@@ -124,11 +124,12 @@ def test_variance_monitor_refuses_the_kind():
         rmm.rmm_variance_stats(X.to(DEV), dY.to(DEV), 32, SORS)
 
 
-@pytest.mark.parametrize("name", ["c3_base_ffn_up", "c3_base_ffn_down"])
+@pytest.mark.parametrize("name", ["c3_base_ffn_up", "c3_base_ffn_down", "c4_large_attn"])
 def test_paired_launch_gives_the_bits_of_the_separate_launches(name):
-    """Where the plain product of a pass leaves compute units idle, the strips of the sketch
-    product share its launch; asking for a single product's stage makes the pass launch them one
-    after the other.  Same kernels' arithmetic either way: every output must agree bit for bit."""
+    """Where the plain product of a pass leaves compute units idle (strips behind its tiles), or
+    runs full rounds beside few long strips (strips in front: the third shape), the strips of the
+    sketch product share its launch; asking for a single product's stage makes the pass launch
+    them one after the other.  Same kernels' arithmetic either way: every output must agree bit for bit."""
     c = synth.CONFIGS[name]
     n, d_in, d_out, k = c["n"], c["d_in"], c["d_out"], c["k"]
     assert rmm.rmm_uses_paired_launch(n, d_in, d_out, k, torch.bfloat16, SORS, binding.OP_FORWARD)
