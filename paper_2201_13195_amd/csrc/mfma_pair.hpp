@@ -34,7 +34,7 @@ struct SorsArgs;
 hipError_t launch_pair_sors(int cfg_a, bool row_indexed_b, const GemmArgs &ga, const SorsArgs &gs, int blocks_a, int chunks,
                             bool sors_first, hipStream_t stream);
 
-// Shared body of the four functions above.
+// Shared body of launch_pair_nt, _nt_split, _nn_large and _nn_split.
 template <typename SA, int BMODE_A, int DA>
 hipError_t launch_pair_impl(int sk_cfg, int kind, const GemmArgs &ga, const GemmArgs &gb, int blocks_a, int tiles_b,
                             int splits, hipStream_t stream) {
