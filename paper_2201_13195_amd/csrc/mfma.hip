@@ -211,7 +211,13 @@ SketchPlan plan_pass_sketch(int64_t n, int64_t d_sk, int64_t d_other, int64_t k)
     const int64_t blocks_a = cfg_a == GEMM_LARGE ? tiles_of(n, d_other, ShapeLarge::BM, ShapeLarge::BN)
                                                  : tiles_of(n, d_other, ShapeSplit::BM, ShapeSplit::BN);
     const int target = paired_sketch_target(blocks_a, 2.0 * n * d_sk * d_other, 2.0 * n * k * d_sk);
-    const SketchPlan paired = plan_sketch(n, d_sk, k, target);
+    SketchPlan paired = plan_sketch(n, d_sk, k, target);
+    if (target == 256) {
+        // Short slices (at most 1024 tokens) pack better into the time the plain product's work-groups
+        // take when there are a quarter more of them; long ones would only add a round.
+        const SketchPlan finer = plan_sketch(n, d_sk, k, 320);
+        if (finer.splits > paired.splits && finer.k_chunk <= 1024) paired = finer;
+    }
     return paired.splits >= 2 ? paired : alone;
 }
 
