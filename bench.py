@@ -341,6 +341,34 @@ def sors_report(run, cfg, steps, dense_ms):
             "step_time_vs_dense_sketch": ms / dense_ms if dense_ms else None}
 
 
+def library_gemm(torch, run, cfg, kernel_ms, reps=30):
+    """The vendor's GEMM library (torch.matmul, bf16) on the three plain products of the layer, same
+    shapes and the same rotating buffers: a yardstick beside the hand-written kernels' own times
+    (`this_build_ms`, event-bracketed the same way), not a part of the path."""
+    k, d_out = cfg["k"], cfg["d_out"]
+    dev = run.sets[0]["X"].device
+    G = torch.randn((k, d_out), device=dev).bfloat16()
+    fl = stage_flops(cfg["n"], cfg["d_in"], d_out, k)
+    products = {
+        "fwd_Y": lambda b: torch.matmul(b["X"], b["W"].t(), out=b["Y"]),
+        "bwd_dX": lambda b: torch.matmul(b["dY"], b["W"], out=b["dX"]),
+        "bwd_dW": lambda b: torch.matmul(G.t(), b["Xp"], out=b["dW"]),
+    }
+    res = {}
+    for name, fn in products.items():
+        for i in range(10):
+            fn(run.sets[i % len(run.sets)])
+        evs = run.new_events(reps)
+        for i, (a, b) in enumerate(evs):
+            a.record()
+            fn(run.sets[i % len(run.sets)])
+            b.record()
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in evs)[reps // 2]
+        res[name] = {"ms": ms, "tflops": fl[name] / (ms * 1e-3) / 1e12, "this_build_ms": kernel_ms[name]}
+    return res
+
+
 def measured_peaks(torch, rmm, dev, reps=5):
     """What a kernel that only issues MFMAs, and one that only reads memory, reach on this machine
     (rmm_probe_mfma on one work-group per compute unit; rmm_probe_read over three rotating 512 MiB
@@ -523,7 +551,13 @@ def main():
     if not args.no_extra_workloads and bf16:
         # the shape the MFMA targets are quoted on, and the other sketch kind at the headline shape
         big = dict(synth.CONFIGS["c4_large_ffn_up"])
-        out["large_shape"] = layer_report(LayerRun(torch, rmm, binding, synth, dev, big, kind, 2), big, args.kind, 20, None)
+        big_run = LayerRun(torch, rmm, binding, synth, dev, big, kind, 2)
+        out["large_shape"] = layer_report(big_run, big, args.kind, 20, None)
+        out["library_gemm"] = {
+            "what": "torch.matmul (the vendor GEMM library) on the plain products, median of 30 event-bracketed calls",
+            "headline_shape": library_gemm(torch, run, cfg, kernel_ms),
+            "large_shape": library_gemm(torch, big_run, big, {s: v["ms"] for s, v in out["large_shape"]["kernels"].items()})}
+        del big_run
         other = rmm.RADEMACHER if kind == rmm.GAUSSIAN else rmm.GAUSSIAN
         out["other_kind"] = layer_report(LayerRun(torch, rmm, binding, synth, dev, cfg, other, args.sets), cfg,
                                          "rademacher" if other == rmm.RADEMACHER else "gaussian", 50, None)
