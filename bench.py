@@ -409,10 +409,23 @@ def measured_peaks(torch, rmm, dev, reps=5):
 
     read()
     hbm = timed(read) / 1e9
-    return {"mfma_bf16_tflops": mfma, "mfma_bf16_tflops_sustained": mfma_sustained, "hbm_read_gbs": hbm, "compute_units": cus,
+    # the same read at the size of the small-k sketch's operand (one launch of about 25 us: ramp-up and
+    # drain weigh more than in the 512 MiB read)
+    del bufs
+    small = [torch.ones(16384 * 4096 * 2, dtype=torch.uint8, device=dev) for _ in range(3)]
+
+    def read_small():
+        turn[0] += 1
+        return rmm.rmm_probe_read(small[turn[0] % 3], cus * 8, sink)
+
+    for _ in range(3):
+        read_small()
+    hbm_small = timed(read_small) / 1e9
+    return {"mfma_bf16_tflops": mfma, "mfma_bf16_tflops_sustained": mfma_sustained, "hbm_read_gbs": hbm,
+            "hbm_read_gbs_128MiB": hbm_small, "compute_units": cus,
             "how": "best of %d launches: 32x32x16 bf16 MFMAs on pseudo-random operands held in registers, one 4-wave work-group per compute unit; "
                    "sustained = launches 31-60 of 60 back to back (about 0.13 s); "
-                   "one streaming read of 512 MiB (three buffers in turn)" % reps}
+                   "one streaming read of 512 MiB, and one of 128 MiB (three buffers in turn each)" % reps}
 
 
 def main():
@@ -592,6 +605,8 @@ def main():
                     kern["frac_of_sustained_mfma"] = kern["tflops"] / mp["mfma_bf16_tflops_sustained"]
         if "sketch_hbm_roofline" in out:
             out["sketch_hbm_roofline"]["frac_of_measured_read"] = out["sketch_hbm_roofline"]["achieved"] / mp["hbm_read_gbs"]
+            out["sketch_hbm_roofline"]["frac_of_measured_read_same_size"] = (
+                out["sketch_hbm_roofline"]["achieved"] / mp["hbm_read_gbs_128MiB"])
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, kind)
     print(json.dumps(out))

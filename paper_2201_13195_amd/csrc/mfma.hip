@@ -147,7 +147,7 @@ hipError_t launch_reduce(const void *ws, bf16_t *out, int64_t k, int64_t d, int 
 }
 
 // The streaming kernel of small sketch sizes: 256-column work-groups, token slices so that about
-// one work-group per compute unit exists; 4 register sets of loads in flight.
+// one work-group per compute unit exists; 2 register sets of loads in flight.
 constexpr int64_t kSmallK = 64;
 int smallk_slices(int64_t n, int64_t d, int64_t *k_chunk) {
     const int64_t col_tiles = (d + 255) / 256, blocks = (n + 127) / 128;
@@ -162,9 +162,9 @@ template <int TM, int KIND>
 hipError_t launch_smallk(const SmallkArgs &g, int slices, hipStream_t stream) {
     const dim3 grid((unsigned)((g.d + 255) / 256), (unsigned)slices);
     if (slices == 1)
-        sketch_smallk_kernel<TM, KIND, 4, OUT_BF16><<<grid, 256, 0, stream>>>(g);
+        sketch_smallk_kernel<TM, KIND, 2, OUT_BF16><<<grid, 256, 0, stream>>>(g);
     else
-        sketch_smallk_kernel<TM, KIND, 4, OUT_F32_PARTIAL><<<grid, 256, 0, stream>>>(g);
+        sketch_smallk_kernel<TM, KIND, 2, OUT_F32_PARTIAL><<<grid, 256, 0, stream>>>(g);
     return hipGetLastError();
 }
 
