@@ -146,25 +146,37 @@ hipError_t launch_reduce(const void *ws, bf16_t *out, int64_t k, int64_t d, int 
     return hipGetLastError();
 }
 
-// The streaming kernel of small sketch sizes: 256-column work-groups, token slices so that about
-// one work-group per compute unit exists; 2 register sets of loads in flight.
+// The streaming kernel of small sketch sizes: token slices so that about one work-group per
+// compute unit exists; 2 register sets of loads in flight.  Work-groups take 256 columns, or 128
+// where that would leave slices of at most 2048 tokens (k <= 32) / 512 tokens (k <= 64): half as many,
+// twice as long slices then halve the partial sums and the final cross-wave sum of a work-group
+// (measured: 26.6 against 27.6 us at 16384 x 4096, k = 32; 11.7 against 15.3 us at 16384 x 1024),
+// while on long slices the wider work-group is ahead (82.8 against 84.6 us at 65536 x 4096).
 constexpr int64_t kSmallK = 64;
-int smallk_slices(int64_t n, int64_t d, int64_t *k_chunk) {
-    const int64_t col_tiles = (d + 255) / 256, blocks = (n + 127) / 128;
+int smallk_slices_for(int64_t n, int64_t d, int64_t bn, int64_t *k_chunk) {
+    const int64_t col_tiles = (d + bn - 1) / bn, blocks = (n + 127) / 128;
     int64_t s = 256 / col_tiles;
     if (s > blocks) s = blocks;
     if (s < 1) s = 1;
     *k_chunk = (blocks + s - 1) / s * 128;
     return (int)((n + *k_chunk - 1) / *k_chunk);
 }
+int64_t smallk_bn(int64_t n, int64_t d, int64_t k) {
+    int64_t k_chunk;
+    (void)smallk_slices_for(n, d, 256, &k_chunk);
+    return k_chunk <= (k <= 32 ? 2048 : 512) ? 128 : 256;
+}
+int smallk_slices(int64_t n, int64_t d, int64_t k, int64_t *k_chunk) {
+    return smallk_slices_for(n, d, smallk_bn(n, d, k), k_chunk);
+}
 
-template <int TM, int KIND>
+template <int TM, int BN, int KIND>
 hipError_t launch_smallk(const SmallkArgs &g, int slices, hipStream_t stream) {
-    const dim3 grid((unsigned)((g.d + 255) / 256), (unsigned)slices);
+    const dim3 grid((unsigned)((g.d + BN - 1) / BN), (unsigned)slices);
     if (slices == 1)
-        sketch_smallk_kernel<TM, KIND, 2, OUT_BF16><<<grid, 256, 0, stream>>>(g);
+        sketch_smallk_kernel<TM, BN, KIND, 2, OUT_BF16><<<grid, 256, 0, stream>>>(g);
     else
-        sketch_smallk_kernel<TM, KIND, 2, OUT_F32_PARTIAL><<<grid, 256, 0, stream>>>(g);
+        sketch_smallk_kernel<TM, BN, KIND, 2, OUT_F32_PARTIAL><<<grid, 256, 0, stream>>>(g);
     return hipGetLastError();
 }
 
@@ -276,7 +288,7 @@ hipError_t launch_xty_sumsq_bf16(const bf16_t *X, const bf16_t *dY, double *part
 
 size_t sketch_workspace_bf16(int64_t n, int64_t d, int64_t k, int64_t d_other) {
     int64_t k_chunk;
-    const int s = k <= kSmallK ? smallk_slices(n, d, &k_chunk)
+    const int s = k <= kSmallK ? smallk_slices(n, d, k, &k_chunk)
                                : (d_other > 0 ? plan_pass_sketch(n, d, d_other, k) : plan_sketch(n, d, k)).splits;
     return s > 1 ? (size_t)s * (size_t)k * (size_t)d * sizeof(float) : 0;
 }
@@ -287,10 +299,16 @@ hipError_t launch_sketch_bf16(const bf16_t *A, bf16_t *out, int64_t n, int64_t d
     if (k <= kSmallK) {  // bound by one pass over A: streaming kernel
         SmallkArgs a{};
         a.A = A, a.n = n, a.d = d, a.k = k, a.st = st;
-        const int slices = smallk_slices(n, d, &a.k_chunk);
+        const int slices = smallk_slices(n, d, k, &a.k_chunk);
         a.C = slices == 1 ? (void *)out : ws, a.alpha = 1.0f / sqrtf((float)k);
-        hipError_t e = k <= 32 ? (kind == 0 ? launch_smallk<1, 0>(a, slices, stream) : launch_smallk<1, 1>(a, slices, stream))
-                               : (kind == 0 ? launch_smallk<2, 0>(a, slices, stream) : launch_smallk<2, 1>(a, slices, stream));
+        const bool narrow = smallk_bn(n, d, k) == 128;
+        hipError_t e;
+        if (k <= 32)
+            e = narrow ? (kind == 0 ? launch_smallk<1, 128, 0>(a, slices, stream) : launch_smallk<1, 128, 1>(a, slices, stream))
+                       : (kind == 0 ? launch_smallk<1, 256, 0>(a, slices, stream) : launch_smallk<1, 256, 1>(a, slices, stream));
+        else
+            e = narrow ? (kind == 0 ? launch_smallk<2, 128, 0>(a, slices, stream) : launch_smallk<2, 128, 1>(a, slices, stream))
+                       : (kind == 0 ? launch_smallk<2, 256, 0>(a, slices, stream) : launch_smallk<2, 256, 1>(a, slices, stream));
         pev.done();
         if (e != hipSuccess || slices == 1) return e;
         return launch_reduce(ws, out, k, d, slices, stream);
