@@ -21,7 +21,6 @@ namespace rmm {
 
 namespace {
 
-
 template <int L>
 struct SorsShape {
     static constexpr int NP = 1 << L;                      // tokens the transform runs over
@@ -30,7 +29,6 @@ struct SorsShape {
     static constexpr int SIGN_WORDS = NP / 32;
     static_assert(L >= 13 && L <= 15, "8192 .. 32768 tokens");
 };
-
 
 // Butterfly stages over W index bits held in registers: v[i] and v[i + h] -> sum and difference.
 template <int W, int C>
