@@ -246,16 +246,23 @@ class LayerRun:
         ws_bytes = max(rmm.rmm_workspace_bytes(n, d_in, d_out, k, tdtype, kind, binding.OP_FORWARD),
                        rmm.rmm_workspace_bytes(n, d_in, d_out, k, tdtype, kind, binding.OP_BACKWARD), 16)
         self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self.bias = self.dbias = None
         self.paired = {"fwd_pair": rmm.rmm_uses_paired_launch(n, d_in, d_out, k, tdtype, kind, binding.OP_FORWARD),
                        "bwd_pair": rmm.rmm_uses_paired_launch(n, d_in, d_out, k, tdtype, kind, binding.OP_BACKWARD)}
 
     def step(self, i, profile=None):
         b, k, c = self.sets[i % len(self.sets)], self.cfg["k"], self.cfg
         # each pass records the events only if the stage id is one of its own
-        self.rmm.rmm_forward(b["X"], b["W"], None, k, self.kind, c["seed"], i, Y=b["Y"], X_proj=b["Xp"], ws=self.ws,
+        self.rmm.rmm_forward(b["X"], b["W"], self.bias, k, self.kind, c["seed"], i, Y=b["Y"], X_proj=b["Xp"], ws=self.ws,
                              profile=profile)
         self.rmm.rmm_backward(b["dY"], b["W"], b["Xp"], self.kind, c["seed"], i, dX=b["dX"], dW=b["dW"], ws=self.ws,
-                              profile=profile)
+                              profile=profile, dbias=self.dbias, need_dbias=self.dbias is not None)
+
+    def with_bias(self, on):
+        """Switch the bias add of the forward pass and the bias gradient of the backward pass on or off."""
+        d_out, t = self.cfg["d_out"], self.sets[0]["X"]
+        self.bias = self.torch.zeros((d_out,), dtype=t.dtype, device=t.device) if on else None
+        self.dbias = self.torch.empty((d_out,), dtype=t.dtype, device=t.device) if on else None
 
     def new_events(self, count):
         evs = []
@@ -570,6 +577,19 @@ def main():
             "what": "torch.matmul (the vendor GEMM library) on the plain products, median of 30 event-bracketed calls",
             "headline_shape": library_gemm(torch, run, cfg, kernel_ms),
             "large_shape": library_gemm(torch, big_run, big, {s: v["ms"] for s, v in out["large_shape"]["kernels"].items()})}
+        # the same steps with the optional bias (Eq. 1) and its gradient db = dY^T 1 (Eq. 3): one more pass over dY
+        bias_ms = {}
+        for name, r in (("headline_shape", run), ("large_shape", big_run)):
+            r.with_bias(True)
+            bias_ms[name] = r.step_ms(50 if r is run else 20)
+            r.with_bias(False)
+        out["with_bias"] = {
+            "what": "ms per step with the bias add in Y and the bias gradient (column sums of dY, HBM-bound) switched on",
+            "headline_shape": {"ms_per_step": bias_ms["headline_shape"], "extra_ms": bias_ms["headline_shape"] - ms_per_step,
+                               "dY_bytes": esize * n * d_out},
+            "large_shape": {"ms_per_step": bias_ms["large_shape"],
+                            "extra_ms": bias_ms["large_shape"] - out["large_shape"]["ms_per_step"],
+                            "dY_bytes": esize * big["n"] * big["d_out"]}}
         del big_run
         other = rmm.RADEMACHER if kind == rmm.GAUSSIAN else rmm.GAUSSIAN
         out["other_kind"] = layer_report(LayerRun(torch, rmm, binding, synth, dev, cfg, other, args.sets), cfg,

@@ -314,3 +314,26 @@ def test_backward_accumulate_over_two_micro_batches(dtype, shape):
         assert e <= tol, (name, e)
     # the accumulated result is not just the second estimate
     assert rel_fro(dW, odW2) > 0.3
+
+
+@pytest.mark.parametrize("dtype,n,d_out", [("bf16", 4096, 3072), ("bf16", 16384, 1024), ("bf16", 16384, 4096),
+                                           ("bf16", 5000, 3080), ("bf16", 777, 264), ("bf16", 300, 67),
+                                           ("f32", 4096, 1536), ("f32", 1000, 132), ("f32", 300, 50)])
+def test_bias_gradient_at_paper_sizes(dtype, n, d_out):
+    """db = dY^T 1 (Eq. 3) against column sums in fp64, on the layer's real dY sizes and on ragged
+    ones: wide matrices (four 16-byte pieces of a row per work-group), narrow ones (one piece),
+    widths that are no multiple of 16 bytes (element-wise kernel); then once more accumulated
+    on top of itself.  The other products of the call are kept tiny (d_in = 8, k = 8)."""
+    d_in, k = 8, 8
+    g = torch.Generator(device="cpu")
+    g.manual_seed(1234 + n + d_out)
+    tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
+    dY = torch.randn((n, d_out), generator=g).to(tdtype).to(DEV)
+    W = torch.randn((d_out, d_in), generator=g).to(tdtype).to(DEV)
+    X_proj = torch.randn((k, d_in), generator=g).to(tdtype).to(DEV)
+    _, dW, db = rmm.rmm_backward(dY, W, X_proj, rmm.RADEMACHER, 5, 6, need_dX=False, need_dbias=True)
+    want = synth.to_f64(dY).sum(axis=0)
+    assert_close(db, want, "db", dtype, label="db %s %dx%d" % (dtype, n, d_out))
+    first = synth.to_f64(db).copy()  # the accumulated value starts from the stored (rounded) one
+    rmm.rmm_backward(dY, W, X_proj, rmm.RADEMACHER, 5, 6, need_dX=False, dW=dW, dbias=db, need_dbias=True, accumulate=True)
+    assert_close(db, want + first, "db", dtype, label="db accumulate")
