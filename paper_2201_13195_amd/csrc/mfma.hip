@@ -39,13 +39,14 @@ int64_t tiles_of(int64_t m, int64_t n, int64_t bm, int64_t bn) { return ((m + bm
 //     from L2 than it delivers at full MFMA rate;
 //   64 x 64 when there are fewer than 65 tiles of 128 x 128 (a quarter of the compute units);
 //   128 x 128 x 64 with two wave groups splitting the contraction when there are at most 256
-//     tiles and the contraction is 1536 or longer (a compute unit then still holds 8 waves);
+//     tiles and the contraction is 768 or longer (a compute unit then still holds 8 waves; at 768
+//     it runs like the 4-wave tile on its own, and its 512 threads allow the paired launch);
 //   128 x 128 x 32 with 4 waves otherwise (two work-groups per compute unit).
 int gemm_cfg(int64_t m, int64_t n, int64_t kk) {
     if (tiles_of(m, n, ShapeLarge::BM, ShapeLarge::BN) >= 160) return GEMM_LARGE;
     const int64_t t128 = tiles_of(m, n, 128, 128);
     if (t128 < 65) return GEMM_TINY;
-    if (t128 <= 256 && kk >= 1536) return GEMM_SPLIT;
+    if (t128 <= 256 && kk >= 768) return GEMM_SPLIT;
     return GEMM_MID;
 }
 

@@ -1,6 +1,6 @@
 """GPU: parity on shapes chosen around every switch point of the host-side kernel selection
 (streaming kernel up to k = 64, LDS-generated sketch tile from d = 1024, 256x256 tiles from 160
-such tiles, two wave groups for few tiles with a contraction of 1536 or more, token slices that
+such tiles, two wave groups for few tiles with a contraction of 768 or more, token slices that
 do not divide n) and on seeded random shapes."""
 import math
 
@@ -21,7 +21,8 @@ BOUNDARY = [
     (700, 1016, 1024, 64), (700, 1024, 1032, 65), (1300, 1032, 1016, 63),   # sketch kernel switches (k, d)
     (2500, 264, 4096, 129), (2560, 4096, 256, 70),                            # 160 / 10 x 16 large tiles in Y / dX
     (2432, 264, 4096, 129),                                                   # 152 large tiles: small-tile path
-    (260, 1536, 136, 1536), (260, 1528, 136, 1528),                           # contraction at / below 1536
+    (260, 1536, 136, 1536), (260, 1528, 136, 1528),                           # long contractions, few tiles
+    (1200, 768, 1024, 100), (1200, 760, 1024, 100),                           # 80 tiles of Y, contraction at / below 768
     (127, 520, 264, 127), (129, 520, 264, 130), (1, 1024, 1024, 1),           # token blocks of 128, n = 1
     (3000, 2056, 8, 410), (3000, 8, 2056, 410),                               # one 8-wide side
 ]
