@@ -102,6 +102,22 @@ def rmm_workspace_bytes(n, d_in, d_out, k, dtype, kind, op):
     return int(load_library().rmm_workspace_bytes(ctypes.byref(_desc(n, d_in, d_out, k, dtype, kind)), int(op)))
 
 
+_PLANS = {}
+
+
+def _plan(n, d_in, d_out, k, dtype, kind, op):
+    """(descriptor by reference, workspace bytes) of a layer call; kept per shape, so that a
+    training loop builds the descriptor and asks the library for the workspace size once."""
+    key = (n, d_in, d_out, k, dtype, kind, op)
+    hit = _PLANS.get(key)
+    if hit is None:
+        if len(_PLANS) > 4096:
+            _PLANS.clear()
+        desc = _desc(n, d_in, d_out, k, dtype, kind)
+        hit = _PLANS[key] = (ctypes.byref(desc), int(load_library().rmm_workspace_bytes(ctypes.byref(desc), int(op))), desc)
+    return hit[0], hit[1]
+
+
 def _ptr(t, name, dtype=None, shape=None, optional=False):
     if t is None:
         if optional:
@@ -115,17 +131,17 @@ def _ptr(t, name, dtype=None, shape=None, optional=False):
         raise TypeError("%s must be %s" % (name, dtype))
     if shape is not None and tuple(t.shape) != tuple(shape):
         raise ValueError("%s must have shape %s, has %s" % (name, tuple(shape), tuple(t.shape)))
-    return ctypes.c_void_p(t.data_ptr())
+    return t.data_ptr()  # (an int where a void* is declared)
 
 
 def _stream(t):
-    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+    return torch.cuda.current_stream(t.device).cuda_stream
 
 
 def _workspace(ws, need, device):
     if ws is None:
         ws = torch.empty(max(need, 16), dtype=torch.uint8, device=device)
-    return ws, ctypes.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size()
+    return ws, ws.data_ptr(), ws.numel() * ws.element_size()
 
 
 def rmm_sketch(A, k, kind, seed, offset, out=None, ws=None, events=None):
@@ -202,10 +218,9 @@ def rmm_forward(X, W, bias, k, kind, seed, offset, Y=None, X_proj=None, ws=None,
         Y = torch.empty((n, d_out), dtype=X.dtype, device=X.device)
     if X_proj is None and need_xproj:
         X_proj = torch.empty((k, d_in), dtype=X.dtype, device=X.device)
-    desc = _desc(n, d_in, d_out, k, X.dtype, kind)
-    need = rmm_workspace_bytes(n, d_in, d_out, k, X.dtype, kind, OP_FORWARD) if need_xproj else 0
-    ws, wsp, wsb = _workspace(ws, need, X.device)
-    rc = load_library().rmm_forward_profiled(ctypes.byref(desc), _State(seed, offset), _ptr(X, "X"),
+    desc, need = _plan(n, d_in, d_out, k, X.dtype, kind, OP_FORWARD)
+    ws, wsp, wsb = _workspace(ws, need if need_xproj else 0, X.device)
+    rc = load_library().rmm_forward_profiled(desc, _State(seed, offset), _ptr(X, "X"),
                                              _ptr(W, "W", X.dtype, (d_out, d_in)),
                                              _ptr(bias, "bias", X.dtype, (d_out,), optional=True),
                                              _ptr(Y, "Y", X.dtype, (n, d_out)),
@@ -230,10 +245,9 @@ def rmm_backward(dY, W, X_proj, kind, seed, offset, need_dX=True, need_dbias=Fal
         dW = torch.empty((d_out, d_in), dtype=dY.dtype, device=dY.device)
     if need_dbias and dbias is None:
         dbias = torch.empty((d_out,), dtype=dY.dtype, device=dY.device)
-    desc = _desc(n, d_in, d_out, k, dY.dtype, kind)
-    need = rmm_workspace_bytes(n, d_in, d_out, k, dY.dtype, kind, OP_BACKWARD)
+    desc, need = _plan(n, d_in, d_out, k, dY.dtype, kind, OP_BACKWARD)
     ws, wsp, wsb = _workspace(ws, need, dY.device)
-    args = (ctypes.byref(desc), _State(seed, offset), _ptr(dY, "dY"), _ptr(W, "W", dY.dtype, (d_out, d_in)),
+    args = (desc, _State(seed, offset), _ptr(dY, "dY"), _ptr(W, "W", dY.dtype, (d_out, d_in)),
             _ptr(X_proj, "X_proj", dY.dtype, (k, d_in)), _ptr(dX, "dX", dY.dtype, (n, d_in), optional=True),
             _ptr(dW, "dW", dY.dtype, (d_out, d_in)), _ptr(dbias, "dbias", dY.dtype, (d_out,), optional=True),
             wsp, wsb, _stream(dY))

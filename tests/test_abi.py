@@ -180,7 +180,8 @@ def test_sors_kind_at_the_boundary(lib):
     assert rmm.rmm_uses_paired_launch(4096, 768, 3072, 410, bf, rmm.SORS, binding.OP_BACKWARD)
     assert rmm.rmm_uses_paired_launch(16384, 1024, 4096, 1638, bf, rmm.SORS, binding.OP_FORWARD)      # few long strips beside 4 rounds of tiles
     assert not rmm.rmm_uses_paired_launch(16384, 1024, 4096, 1638, bf, rmm.SORS, binding.OP_BACKWARD) # as many strip groups as CUs
-    assert not rmm.rmm_uses_paired_launch(4096, 768, 768, 410, bf, rmm.SORS, binding.OP_FORWARD)      # 256-thread plain tiles
+    assert rmm.rmm_uses_paired_launch(4096, 768, 768, 410, bf, rmm.SORS, binding.OP_FORWARD)          # 192 split tiles
+    assert not rmm.rmm_uses_paired_launch(4096, 512, 768, 410, bf, rmm.SORS, binding.OP_FORWARD)      # 256-thread plain tiles
     assert not rmm.rmm_uses_paired_launch(2048, 768, 3072, 410, bf, rmm.SORS, binding.OP_FORWARD)     # a single chunk
     assert not rmm.rmm_uses_paired_launch(4096, 768, 3072, 2049, bf, rmm.SORS, binding.OP_FORWARD)    # too many sketch columns
     assert rmm.rmm_uses_paired_launch(4096, 768, 3072, 410, bf, rmm.GAUSSIAN, binding.OP_BACKWARD)

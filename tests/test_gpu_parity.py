@@ -9,7 +9,7 @@ import pytest
 import torch
 
 import paper_2201_13195_amd as rmm
-from paper_2201_13195_amd import synth
+from paper_2201_13195_amd import binding, synth
 from oracle import philox as o_philox
 from oracle import rmm as o_rmm
 from oracle import sketch as o_sketch
@@ -337,3 +337,26 @@ def test_bias_gradient_at_paper_sizes(dtype, n, d_out):
     first = synth.to_f64(db).copy()  # the accumulated value starts from the stored (rounded) one
     rmm.rmm_backward(dY, W, X_proj, rmm.RADEMACHER, 5, 6, need_dX=False, dW=dW, dbias=db, need_dbias=True, accumulate=True)
     assert_close(db, want + first, "db", dtype, label="db accumulate")
+
+
+@pytest.mark.parametrize("kind", [rmm.GAUSSIAN, rmm.RADEMACHER])
+@pytest.mark.parametrize("name", ["c2_base_attn", "c3_base_ffn_up", "c3_base_ffn_down", "c4_large_ffn_up"])
+def test_paired_launch_gives_the_bits_of_the_separate_launches(name, kind):
+    """At these shapes a pass runs its plain product and its sketch product as one launch; asking
+    for a single product's stage makes it launch them one after the other, with the same token
+    slices.  Same tiles, same order of additions: every output must agree bit for bit."""
+    c = synth.CONFIGS[name]
+    n, d_in, d_out, k = c["n"], c["d_in"], c["d_out"], c["k"]
+    assert rmm.rmm_uses_paired_launch(n, d_in, d_out, k, torch.bfloat16, kind, binding.OP_FORWARD)
+    assert rmm.rmm_uses_paired_launch(n, d_in, d_out, k, torch.bfloat16, kind, binding.OP_BACKWARD)
+    X, W, dY = synth.layer_inputs(n, d_in, d_out, "bf16", c["seeds"])
+    Xd, Wd, dYd = X.to(DEV), W.to(DEV), dY.to(DEV)
+    Y0, Xp0 = rmm.rmm_forward(Xd, Wd, None, k, kind, 9, 1)
+    dX0, dW0, _ = rmm.rmm_backward(dYd, Wd, Xp0, kind, 9, 1)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(); b.record()
+    torch.cuda.synchronize()
+    Y1, Xp1 = rmm.rmm_forward(Xd, Wd, None, k, kind, 9, 1, profile=(binding.STAGE_FWD_Y, a, b))
+    dX1, dW1, _ = rmm.rmm_backward(dYd, Wd, Xp1, kind, 9, 1, profile=(binding.STAGE_BWD_DX, a, b))
+    torch.cuda.synchronize()
+    assert torch.equal(Y0, Y1) and torch.equal(Xp0, Xp1) and torch.equal(dX0, dX1) and torch.equal(dW0, dW1)

@@ -124,7 +124,7 @@ def test_variance_monitor_refuses_the_kind():
         rmm.rmm_variance_stats(X.to(DEV), dY.to(DEV), 32, SORS)
 
 
-@pytest.mark.parametrize("name", ["c3_base_ffn_up", "c3_base_ffn_down", "c4_large_attn"])
+@pytest.mark.parametrize("name", ["c2_base_attn", "c3_base_ffn_up", "c3_base_ffn_down", "c4_large_attn"])
 def test_paired_launch_gives_the_bits_of_the_separate_launches(name):
     """Where the plain product of a pass leaves compute units idle (strips behind its tiles), or
     runs full rounds beside few long strips (strips in front: the third shape), the strips of the
