@@ -512,9 +512,9 @@ def main():
     dom_idx = PAIR_STAGE_ID.get(dominant, KERNEL_STAGE_ID.get(dominant))
 
     # ---- timed region: exactly `steps` steps, events around the dominant kernel of every step
-    # (an event pair costs the stream about 5 us, 5 % of a step at the headline shape: every fourth step
+    # (an event pair costs the stream about 5 us, 5 % of a step at the headline shape: every tenth step
     # carries one, which still samples the dominant kernel all over the timed region)
-    EVERY = 4
+    EVERY = 10
     evs = run.new_events((args.steps + EVERY - 1) // EVERY)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
