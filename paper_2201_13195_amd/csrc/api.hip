@@ -207,6 +207,12 @@ int backward_impl(const rmm_layer_desc_t *d, SketchState st, const void *dY, con
                                 RMM_STAGE_BWD_G_PRODUCT, d->d_in);
         if (rc != RMM_OK) return rc;
     }
+    if (mfma && dbias != nullptr && ev.stage != RMM_STAGE_BWD_DW && ev.stage != RMM_STAGE_BWD_DBIAS) {
+        // dW and db in one launch (an event request for either stage keeps them apart)
+        e = launch_dw_colsum_bf16((const bf16_t *)G, (const bf16_t *)X_proj, (bf16_t *)dW, d->k, d->d_in, d->d_out,
+                                  (const bf16_t *)dY, (bf16_t *)dbias, d->n, stream, accumulate);
+        return e == hipSuccess ? RMM_OK : RMM_ERR_LAUNCH;
+    }
     {   // dW = G^T X_proj: A(r, kk) = G[kk][r], B(kk, c) = X_proj[kk][c]
         StageScope scope(ev, RMM_STAGE_BWD_DW, stream);
         e = mfma ? launch_dw_bf16((const bf16_t *)G, (const bf16_t *)X_proj, (bf16_t *)dW, d->k, d->d_in, d->d_out,
@@ -227,7 +233,7 @@ int backward_impl(const rmm_layer_desc_t *d, SketchState st, const void *dY, con
 
 extern "C" {
 
-int rmm_version(void) { return 305; }
+int rmm_version(void) { return 306; }
 
 const char *rmm_status_string(int status) {
     switch (status) {

@@ -63,6 +63,10 @@ hipError_t launch_linear_nn_bf16(const bf16_t *dY, const bf16_t *W, bf16_t *dX, 
                                  int64_t d_out, hipStream_t stream);
 hipError_t launch_dw_bf16(const bf16_t *G, const bf16_t *X_proj, bf16_t *dW, int64_t k, int64_t d_in, int64_t d_out,
                           hipStream_t stream, bool accumulate = false);
+// dW together with db = column sums of dY (n x d_out, 16-byte aligned, d_out a multiple of 8) in
+// one launch; same results as launch_dw_bf16 followed by launch_colsum, bit for bit.
+hipError_t launch_dw_colsum_bf16(const bf16_t *G, const bf16_t *X_proj, bf16_t *dW, int64_t k, int64_t d_in, int64_t d_out,
+                                 const bf16_t *dY, bf16_t *dbias, int64_t n, hipStream_t stream, bool accumulate = false);
 // `d_other` > 0 says that the sketch product belongs to a layer pass whose plain product has an
 // n x d_other output (forward: d = d_in, d_other = d_out; backward: d = d_out, d_other = d_in): the
 // token slicing is then the one the paired launch of that pass uses, so that the separate and the

@@ -266,6 +266,32 @@ hipError_t launch_dw_bf16(const bf16_t *G, const bf16_t *X_proj, bf16_t *dW, int
     return launch_gemm<A_MCONTIG, B_NCONTIG, OUT_BF16>(gemm_cfg(g.M, g.N, g.K), g, stream);
 }
 
+template <typename S>
+static hipError_t launch_dw_colsum(const GemmArgs &g, const ColsumArgs &c, hipStream_t stream) {
+    const int blocks_a = (int)tiles_of(g.M, g.N, S::BM, S::BN);
+    const dim3 grid((unsigned)(blocks_a + colsum_blocks(c.d, 2)));
+    if (std::is_same<S, ShapeLarge>::value || plain_depth(g.K, S::BK) == 3)
+        dw_colsum_kernel<S, 3><<<grid, S::THREADS, 0, stream>>>(g, c, blocks_a);
+    else
+        dw_colsum_kernel<S, 4><<<grid, S::THREADS, 0, stream>>>(g, c, blocks_a);
+    return hipGetLastError();
+}
+
+hipError_t launch_dw_colsum_bf16(const bf16_t *G, const bf16_t *X_proj, bf16_t *dW, int64_t k, int64_t d_in, int64_t d_out,
+                                 const bf16_t *dY, bf16_t *dbias, int64_t n, hipStream_t stream, bool accumulate) {
+    GemmArgs g{};
+    g.accumulate = accumulate ? 1 : 0;
+    g.A = G, g.lda = d_out, g.B = X_proj, g.ldb = d_in, g.C = dW, g.ldc = d_in, g.bias = nullptr;
+    g.M = d_out, g.N = d_in, g.K = k, g.alpha = 1.0f, g.k_chunk = (k + 127) / 128 * 128;
+    const ColsumArgs c{dY, dbias, n, d_out, accumulate ? 1 : 0, colsum_lpr(d_out, 2)};
+    switch (gemm_cfg(g.M, g.N, g.K)) {  // the tile dW runs with on its own
+        case GEMM_LARGE: return launch_dw_colsum<ShapeLarge>(g, c, stream);
+        case GEMM_SPLIT: return launch_dw_colsum<ShapeSplit>(g, c, stream);
+        case GEMM_TINY: return launch_dw_colsum<ShapeTiny>(g, c, stream);
+        default: return launch_dw_colsum<ShapeMid>(g, c, stream);
+    }
+}
+
 // |X^T dY|_F^2 per tile for the variance monitors: the dW-type product (both operands stored
 // [token][feature]) with the squared-norm epilogue; the tile menu of the other products without
 // its 64 x 64 entry.

@@ -6,7 +6,7 @@
 // test hooks.  They are written for clarity: one 64x64 output tile per 256-thread
 // work-group, 4x4 outputs per thread, operands staged through LDS 16 contraction
 // steps at a time.  The bf16 hot path lives in the MFMA kernels.
-#include "common.hpp"
+#include "colsum.hpp"
 
 namespace rmm {
 
@@ -137,60 +137,11 @@ __global__ void __launch_bounds__(256) gemm_plain_kernel(ASrc A, BSrc B, Tout *_
     }
 }
 
-// out[c] = sum_r A[r][c] (+ the old out[c]).  One pass over A, bound by HBM.  A work-group owns
-// LPR x 16 bytes of every row (LPR = 4: 32 bf16 or 16 fp32 columns): thread t takes 16 bytes of
-// rows t / LPR, t / LPR + 256 / LPR, ..., eight loads in flight, and keeps fp32 sums of its 8 (4)
-// columns; the row groups of a column are then added through LDS in fixed order.  Column blocks
-// that share a 128-byte line of A are numbered onto one XCD (work-groups are dealt round-robin to
-// the 8 XCDs, each with its own L2), so HBM sees every line once.  Narrow matrices take fewer
-// lanes per row, so that enough work-groups exist to pull the matrix in.
-template <typename T, int LPR>
-__global__ void __launch_bounds__(256) colsum_kernel(const T *__restrict__ A, T *__restrict__ out, int64_t n,
-                                                     int64_t d, bool accumulate) {
-    constexpr int VEC = 16 / (int)sizeof(T), BC = VEC * LPR, RPP = 256 / LPR, U = 8;
-    __shared__ float part[RPP][BC + 1];
-    int64_t blk = blockIdx.x;
-    {
-        const int64_t groups = gridDim.x, per = groups / 8, rem = groups % 8, x = blk % 8, r = blk / 8;
-        blk = x * per + (x < rem ? x : rem) + r;
-    }
-    const int cq = threadIdx.x % LPR, rg = threadIdx.x / LPR;
-    const int64_t c = blk * BC + cq * VEC;
-    float acc[VEC];
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
-    if (c < d) {  // d is a multiple of VEC here
-        for (int64_t r0 = rg; r0 < n; r0 += (int64_t)RPP * U) {
-            uint4 v[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (r0 + u * RPP < n) v[u] = *reinterpret_cast<const uint4 *>(A + (r0 + u * RPP) * d + c);
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (r0 + u * RPP >= n) break;
-                const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    if constexpr (sizeof(T) == 2) {
-                        acc[2 * q] += __uint_as_float(w[q] << 16);
-                        acc[2 * q + 1] += __uint_as_float(w[q] & 0xFFFF0000u);
-                    } else {
-                        acc[q] += __uint_as_float(w[q]);
-                    }
-                }
-            }
-        }
-    }
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) part[rg][cq * VEC + e] = acc[e];
-    __syncthreads();
-    const int64_t col = blk * BC + threadIdx.x;
-    if (threadIdx.x < BC && col < d) {
-        float s = 0.0f;
-        for (int g = 0; g < RPP; ++g) s += part[g][threadIdx.x];
-        if (accumulate) s += load_f32<T>(out + col);
-        store_f32<T>(out + col, s);
-    }
+// Column sums with 16-byte loads (colsum.hpp) as a kernel of its own.
+template <typename T>
+__global__ void __launch_bounds__(256) colsum_kernel(ColsumArgs g) {
+    __shared__ float lds[kColsumLdsFloats];
+    colsum_body<T>(g, lds, blockIdx.x, gridDim.x);
 }
 
 // The same for widths or addresses that rule out 16-byte loads: 64 columns per work-group, one
@@ -256,15 +207,9 @@ hipError_t launch_sketch_plain(const Tin *A, Tout *out, int64_t n, int64_t d, in
 
 template <typename T>
 hipError_t launch_colsum(const T *A, T *out, int64_t n, int64_t d, hipStream_t stream, bool accumulate) {
-    constexpr int64_t VEC = 16 / (int64_t)sizeof(T);
-    if (d % VEC == 0 && (reinterpret_cast<uintptr_t>(A) & 15u) == 0) {
-        // 16-byte pieces per row: four per work-group where that still gives 96 work-groups, else one
-        // (measured at 16384 x 1024 bf16: 15 us with one, 21 with two, 41 with four)
-        const int64_t vecs = d / VEC;
-        if (vecs >= 384)
-            colsum_kernel<T, 4><<<(unsigned)((vecs + 3) / 4), 256, 0, stream>>>(A, out, n, d, accumulate);
-        else
-            colsum_kernel<T, 1><<<(unsigned)vecs, 256, 0, stream>>>(A, out, n, d, accumulate);
+    if (colsum_wide_ok(A, d, sizeof(T))) {
+        const ColsumArgs g{A, out, n, d, accumulate ? 1 : 0, colsum_lpr(d, sizeof(T))};
+        colsum_kernel<T><<<(unsigned)colsum_blocks(d, sizeof(T)), 256, 0, stream>>>(g);
     } else
         colsum_narrow_kernel<T><<<(unsigned)((d + 63) / 64), 256, 0, stream>>>(A, out, n, d, accumulate);
     return hipGetLastError();

@@ -360,3 +360,26 @@ def test_paired_launch_gives_the_bits_of_the_separate_launches(name, kind):
     dX1, dW1, _ = rmm.rmm_backward(dYd, Wd, Xp1, kind, 9, 1, profile=(binding.STAGE_BWD_DX, a, b))
     torch.cuda.synchronize()
     assert torch.equal(Y0, Y1) and torch.equal(Xp0, Xp1) and torch.equal(dX0, dX1) and torch.equal(dW0, dW1)
+
+
+@pytest.mark.parametrize("shape", [(4096, 768, 3072, 410), (4096, 3072, 768, 410), (2000, 264, 520, 100), (300, 1544, 1608, 1550)])
+def test_weight_and_bias_gradient_in_one_launch_give_the_bits_of_two(shape):
+    """With a bias gradient the backward pass computes dW and db in one launch; asking for the dW
+    stage's events makes it use the two kernels of their own.  Same tiles, same order of additions."""
+    n, d_in, d_out, k = shape
+    X, W, dY = synth.layer_inputs(n, d_in, d_out, "bf16", (61, 62, 63))
+    Xd, Wd, dYd = X.to(DEV), W.to(DEV), dY.to(DEV)
+    _, Xp = rmm.rmm_forward(Xd, Wd, None, k, rmm.GAUSSIAN, 3, 4)
+    dX0, dW0, db0 = rmm.rmm_backward(dYd, Wd, Xp, rmm.GAUSSIAN, 3, 4, need_dbias=True)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(); b.record()
+    torch.cuda.synchronize()
+    dX1, dW1, db1 = rmm.rmm_backward(dYd, Wd, Xp, rmm.GAUSSIAN, 3, 4, need_dbias=True, profile=(binding.STAGE_BWD_DW, a, b))
+    torch.cuda.synchronize()
+    assert torch.equal(dX0, dX1) and torch.equal(dW0, dW1) and torch.equal(db0, db1)
+    assert_close(db0, synth.to_f64(dY).sum(axis=0), "db", "bf16", label="db fused %s" % (shape,))
+    # accumulated on top of itself, again both ways
+    dWa, dba = dW0.clone(), db0.clone()
+    rmm.rmm_backward(dYd, Wd, Xp, rmm.GAUSSIAN, 3, 4, dW=dWa, dbias=dba, need_dbias=True, accumulate=True)
+    assert_close(dba, synth.to_f64(dY).sum(axis=0) + synth.to_f64(db0), "db", "bf16", label="db fused accumulate")
+    assert_close(dWa, 2.0 * synth.to_f64(dW0), "dW", "bf16", label="dW fused accumulate")
