@@ -186,11 +186,15 @@ int backward_impl(const rmm_layer_desc_t *d, SketchState st, const void *dY, con
     }
     const bool paired = paired_sors || (sliced_sketch(d) && dX != nullptr && !separate_stage(ev.stage) &&
                                         backward_pair_available(d->n, d->d_in, d->d_out, d->k));
+    const bool own_db_stage = ev.stage == RMM_STAGE_BWD_DW || ev.stage == RMM_STAGE_BWD_DBIAS;
+    bool db_done = false;
     if (paired && !paired_sors) {
         const bool timed = ev.stage == RMM_STAGE_BWD_PAIR;
+        db_done = dbias != nullptr && !own_db_stage && backward_pair_takes_colsum(d->n, d->d_in, d->d_out, d->k);
         e = launch_backward_pair_bf16((const bf16_t *)dY, (const bf16_t *)W, (bf16_t *)dX, (bf16_t *)G, d->n, d->d_in,
                                       d->d_out, d->k, d->kind, st, (char *)ws + g_bytes(d), stream,
-                                      timed ? ev.begin : nullptr, timed ? ev.end : nullptr);
+                                      timed ? ev.begin : nullptr, timed ? ev.end : nullptr,
+                                      db_done ? (bf16_t *)dbias : nullptr, accumulate);
         if (e != hipSuccess) return RMM_ERR_LAUNCH;
     }
     if (!paired && dX != nullptr) {  // dX = dY W: B(kk, c) = W[kk][c]
@@ -207,7 +211,7 @@ int backward_impl(const rmm_layer_desc_t *d, SketchState st, const void *dY, con
                                 RMM_STAGE_BWD_G_PRODUCT, d->d_in);
         if (rc != RMM_OK) return rc;
     }
-    if (mfma && dbias != nullptr && ev.stage != RMM_STAGE_BWD_DW && ev.stage != RMM_STAGE_BWD_DBIAS) {
+    if (mfma && dbias != nullptr && !db_done && !own_db_stage) {
         // dW and db in one launch (an event request for either stage keeps them apart)
         e = launch_dw_colsum_bf16((const bf16_t *)G, (const bf16_t *)X_proj, (bf16_t *)dW, d->k, d->d_in, d->d_out,
                                   (const bf16_t *)dY, (bf16_t *)dbias, d->n, stream, accumulate);
@@ -221,7 +225,7 @@ int backward_impl(const rmm_layer_desc_t *d, SketchState st, const void *dY, con
                                            (const T *)nullptr, d->d_out, d->d_in, d->k, 1.0f, stream, accumulate);
         if (e != hipSuccess) return RMM_ERR_LAUNCH;
     }
-    if (dbias != nullptr) {
+    if (dbias != nullptr && !db_done) {
         StageScope scope(ev, RMM_STAGE_BWD_DBIAS, stream);
         e = launch_colsum<T>((const T *)dY, (T *)dbias, d->n, d->d_out, stream, accumulate);
         if (e != hipSuccess) return RMM_ERR_LAUNCH;
@@ -233,7 +237,7 @@ int backward_impl(const rmm_layer_desc_t *d, SketchState st, const void *dY, con
 
 extern "C" {
 
-int rmm_version(void) { return 306; }
+int rmm_version(void) { return 307; }
 
 const char *rmm_status_string(int status) {
     switch (status) {

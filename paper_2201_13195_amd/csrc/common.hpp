@@ -86,9 +86,13 @@ hipError_t launch_forward_pair_bf16(const bf16_t *X, const bf16_t *W, const bf16
                                     int64_t n, int64_t d_in, int64_t d_out, int64_t k, int kind, SketchState st, void *ws,
                                     hipStream_t stream, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
 bool backward_pair_available(int64_t n, int64_t d_in, int64_t d_out, int64_t k);
+// With `dbias` the launch also takes the column sums of dY (the bias gradient), on the compute units
+// its last round leaves idle; backward_pair_takes_colsum() says where that beats the launch of dW.
 hipError_t launch_backward_pair_bf16(const bf16_t *dY, const bf16_t *W, bf16_t *dX, bf16_t *G, int64_t n, int64_t d_in,
                                      int64_t d_out, int64_t k, int kind, SketchState st, void *ws, hipStream_t stream,
-                                     hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
+                                     hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr, bf16_t *dbias = nullptr,
+                                     bool accumulate_dbias = false);
+bool backward_pair_takes_colsum(int64_t n, int64_t d_in, int64_t d_out, int64_t k);
 
 // SORS sketch kind, bf16 (sors.hip): signs, Walsh-Hadamard transform along the tokens and row
 // selection in one kernel, no workspace.  Usable when sors_fast_ok(): d a multiple of 8 and at most

@@ -380,20 +380,40 @@ bool backward_pair_available(int64_t n, int64_t d_in, int64_t d_out, int64_t k) 
     return pair_ok(cfg, cfg == GEMM_SPLIT ? plain_depth(d_out, ShapeSplit::BK) : 3, plan_sketch(n, d_out, k));
 }
 
+// Where the bias gradient goes in a backward pass that has the paired launch: into the launch of
+// dW when that leaves at least 64 compute units idle (dW is short and mostly latency); otherwise
+// into the paired launch when its last round leaves at least 16 idle (the sketch work-groups of
+// that round run for long, and dY is being read there anyway); otherwise into the launch of dW.
+bool backward_pair_takes_colsum(int64_t n, int64_t d_in, int64_t d_out, int64_t k) {
+    if (!backward_pair_available(n, d_in, d_out, k)) return false;
+    const int dw_cfg = gemm_cfg(d_out, d_in, k);
+    const int64_t dw_tiles = dw_cfg == GEMM_LARGE ? tiles_of(d_out, d_in, ShapeLarge::BM, ShapeLarge::BN)
+                             : dw_cfg == GEMM_TINY ? tiles_of(d_out, d_in, ShapeTiny::BM, ShapeTiny::BN)
+                                                   : tiles_of(d_out, d_in, 128, 128);
+    if ((256 - dw_tiles % 256) % 256 >= 64) return false;
+    const int64_t blocks_a = gemm_cfg(n, d_in, d_out) == GEMM_LARGE ? tiles_of(n, d_in, ShapeLarge::BM, ShapeLarge::BN)
+                                                                    : tiles_of(n, d_in, ShapeSplit::BM, ShapeSplit::BN);
+    const SketchPlan p = plan_pass_sketch(n, d_out, d_in, k);
+    const int64_t total = blocks_a + p.tiles * p.splits;
+    return (256 - total % 256) % 256 >= 16;
+}
+
 hipError_t launch_backward_pair_bf16(const bf16_t *dY, const bf16_t *W, bf16_t *dX, bf16_t *G, int64_t n, int64_t d_in,
                                      int64_t d_out, int64_t k, int kind, SketchState st, void *ws, hipStream_t stream,
-                                     hipEvent_t ev_begin, hipEvent_t ev_end) {
+                                     hipEvent_t ev_begin, hipEvent_t ev_end, bf16_t *dbias, bool accumulate_dbias) {
     const GemmArgs ga = args_nn(dY, W, dX, n, d_in, d_out);
     const SketchPlan p = plan_pass_sketch(n, d_out, d_in, k);
     const GemmArgs gb = args_sketch(dY, n, d_out, k, st, p, G, ws);
+    const ColsumArgs gc{dY, dbias, n, d_out, accumulate_dbias ? 1 : 0, colsum_lpr(d_out, 2)};
+    const ColsumArgs *gcp = dbias != nullptr ? &gc : nullptr;
     EventPair pev(ev_begin, ev_end, stream);
     hipError_t e;
     if (gemm_cfg(ga.M, ga.N, ga.K) == GEMM_LARGE)
         e = launch_pair_nn_large(p.cfg, kind, ga, gb, (int)tiles_of(ga.M, ga.N, ShapeLarge::BM, ShapeLarge::BN), (int)p.tiles,
-                                 p.splits, stream);
+                                 p.splits, stream, gcp);
     else
         e = launch_pair_nn_split(p.cfg, kind, ga, gb, (int)tiles_of(ga.M, ga.N, ShapeSplit::BM, ShapeSplit::BN), (int)p.tiles,
-                                 p.splits, stream);
+                                 p.splits, stream, gcp);
     pev.done();
     if (e != hipSuccess) return e;
     return launch_reduce(ws, G, k, d_out, p.splits, stream);

@@ -17,14 +17,15 @@ enum { SK_NARROW = 0, SK_WIDE = 1, SK_WIDE64 = 2, SK_MID64 = 3, SK_MID = 4 };
 //   nn_large: dX = dY W, 256 x 256 tiles (GEMM_LARGE, depth 3)
 //   nn_split: dX = dY W, 128 x 128 x 64 tiles with two wave groups (GEMM_SPLIT, depth 4)
 // sk_cfg is one of SK_WIDE, SK_WIDE64, SK_MID64, SK_MID; anything else returns hipErrorInvalidValue.
+// `gc`, if not null, adds the column blocks of a column-sum problem (colsum.hpp) behind the sketch work-groups.
 hipError_t launch_pair_nt(int sk_cfg, int kind, const GemmArgs &ga, const GemmArgs &gb, int blocks_a, int tiles_b,
-                          int splits, hipStream_t stream);
+                          int splits, hipStream_t stream, const ColsumArgs *gc = nullptr);
 hipError_t launch_pair_nt_split(int sk_cfg, int kind, const GemmArgs &ga, const GemmArgs &gb, int blocks_a, int tiles_b,
-                                int splits, hipStream_t stream);
+                                int splits, hipStream_t stream, const ColsumArgs *gc = nullptr);
 hipError_t launch_pair_nn_large(int sk_cfg, int kind, const GemmArgs &ga, const GemmArgs &gb, int blocks_a, int tiles_b,
-                                int splits, hipStream_t stream);
+                                int splits, hipStream_t stream, const ColsumArgs *gc = nullptr);
 hipError_t launch_pair_nn_split(int sk_cfg, int kind, const GemmArgs &ga, const GemmArgs &gb, int blocks_a, int tiles_b,
-                                int splits, hipStream_t stream);
+                                int splits, hipStream_t stream, const ColsumArgs *gc = nullptr);
 
 // The same for the SORS sketch kind (mfma_pair_sors.hip): `gs` describes the sketch product, whose
 // strips go two to a work-group; cfg_a is GEMM_LARGE (depth 3) or GEMM_SPLIT (depth 4), row_indexed_b
@@ -37,17 +38,19 @@ hipError_t launch_pair_sors(int cfg_a, bool row_indexed_b, const GemmArgs &ga, c
 // Shared body of launch_pair_nt, _nt_split, _nn_large and _nn_split.
 template <typename SA, int BMODE_A, int DA>
 hipError_t launch_pair_impl(int sk_cfg, int kind, const GemmArgs &ga, const GemmArgs &gb, int blocks_a, int tiles_b,
-                            int splits, hipStream_t stream) {
-    const dim3 grid((unsigned)(blocks_a + tiles_b * splits));
+                            int splits, hipStream_t stream, const ColsumArgs *gc) {
+    const int sketch_blocks = tiles_b * splits;
+    const ColsumArgs c = gc != nullptr ? *gc : ColsumArgs{};
+    const dim3 grid((unsigned)(blocks_a + sketch_blocks + (gc != nullptr ? colsum_blocks(c.d, 2) : 0)));
     const int key = sk_cfg * 2 + (kind != 0 ? 1 : 0);
 #define RMM_PAIR_CASE(CFG, SHAPE)                                                                                      \
     case CFG * 2:                                                                                                      \
         gemm_pair_kernel<SA, A_KCONTIG, BMODE_A, DA, SHAPE, A_GAUSS_LDS, 3>                                           \
-            <<<grid, SA::THREADS, 0, stream>>>(ga, gb, blocks_a, tiles_b);                                             \
+            <<<grid, SA::THREADS, 0, stream>>>(ga, gb, blocks_a, tiles_b, sketch_blocks, c);                                             \
         break;                                                                                                         \
     case CFG * 2 + 1:                                                                                                  \
         gemm_pair_kernel<SA, A_KCONTIG, BMODE_A, DA, SHAPE, A_RADEM_LDS, 3>                                           \
-            <<<grid, SA::THREADS, 0, stream>>>(ga, gb, blocks_a, tiles_b);                                             \
+            <<<grid, SA::THREADS, 0, stream>>>(ga, gb, blocks_a, tiles_b, sketch_blocks, c);                                             \
         break;
     switch (key) {
         RMM_PAIR_CASE(SK_WIDE, ShapeSkWide)

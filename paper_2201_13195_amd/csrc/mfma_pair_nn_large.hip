@@ -4,8 +4,8 @@
 namespace rmm {
 
 hipError_t launch_pair_nn_large(int sk_cfg, int kind, const GemmArgs &ga, const GemmArgs &gb, int blocks_a, int tiles_b,
-                            int splits, hipStream_t stream) {
-    return launch_pair_impl<ShapeLarge, B_NCONTIG, 3>(sk_cfg, kind, ga, gb, blocks_a, tiles_b, splits, stream);
+                            int splits, hipStream_t stream, const ColsumArgs *gc) {
+    return launch_pair_impl<ShapeLarge, B_NCONTIG, 3>(sk_cfg, kind, ga, gb, blocks_a, tiles_b, splits, stream, gc);
 }
 
 }  // namespace rmm

@@ -4,8 +4,8 @@
 namespace rmm {
 
 hipError_t launch_pair_nt_split(int sk_cfg, int kind, const GemmArgs &ga, const GemmArgs &gb, int blocks_a, int tiles_b,
-                            int splits, hipStream_t stream) {
-    return launch_pair_impl<ShapeSplit, B_KCONTIG, 4>(sk_cfg, kind, ga, gb, blocks_a, tiles_b, splits, stream);
+                            int splits, hipStream_t stream, const ColsumArgs *gc) {
+    return launch_pair_impl<ShapeSplit, B_KCONTIG, 4>(sk_cfg, kind, ga, gb, blocks_a, tiles_b, splits, stream, gc);
 }
 
 }  // namespace rmm

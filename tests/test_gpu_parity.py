@@ -362,10 +362,13 @@ def test_paired_launch_gives_the_bits_of_the_separate_launches(name, kind):
     assert torch.equal(Y0, Y1) and torch.equal(Xp0, Xp1) and torch.equal(dX0, dX1) and torch.equal(dW0, dW1)
 
 
-@pytest.mark.parametrize("shape", [(4096, 768, 3072, 410), (4096, 3072, 768, 410), (2000, 264, 520, 100), (300, 1544, 1608, 1550)])
+@pytest.mark.parametrize("shape", [(4096, 768, 3072, 410), (4096, 3072, 768, 410), (2000, 264, 520, 100), (300, 1544, 1608, 1550),
+                                   (16384, 1024, 4096, 1638), (16384, 4096, 1024, 1638), (16384, 1024, 1024, 1638)])
 def test_weight_and_bias_gradient_in_one_launch_give_the_bits_of_two(shape):
-    """With a bias gradient the backward pass computes dW and db in one launch; asking for the dW
-    stage's events makes it use the two kernels of their own.  Same tiles, same order of additions."""
+    """With a bias gradient the backward pass takes the column sums of dY in the launch of dW or,
+    where dW fills the chip (the last three shapes), in the paired launch of dX and the sketch
+    product; asking for the dW stage's events makes it use the kernel of their own.  Same tiles,
+    same order of additions."""
     n, d_in, d_out, k = shape
     X, W, dY = synth.layer_inputs(n, d_in, d_out, "bf16", (61, 62, 63))
     Xd, Wd, dYd = X.to(DEV), W.to(DEV), dY.to(DEV)
