@@ -107,11 +107,11 @@ SketchPlan plan_sketch(int64_t n, int64_t d, int64_t k, int target_wgs = 256) {
 }
 
 GemmArgs args_sketch(const bf16_t *A, int64_t n, int64_t d, int64_t k, SketchState st, const SketchPlan &p, bf16_t *out,
-                     void *ws) {
+                     void *ws, bool always_partial = false) {
     GemmArgs g{};
     g.A = nullptr, g.lda = 0, g.B = A, g.ldb = d, g.bias = nullptr;
     g.M = k, g.N = d, g.K = n, g.st = st, g.ldc = d, g.k_chunk = p.k_chunk;
-    if (p.splits == 1) {
+    if (p.splits == 1 && !always_partial) {
         g.C = out, g.alpha = 1.0f / sqrtf((float)k);
     } else {
         g.C = ws, g.alpha = 1.0f, g.split_stride = k * d;
@@ -198,8 +198,13 @@ struct EventPair {
 // The paired launch exists for a plain product on 256 x 256 tiles, or on the 128 x 128 x 64 split
 // tiles at prefetch depth 4 (both run with 512 threads, like the sketch kernels), next to a sketch
 // product with an LDS-generated tile and at least two token slices.
+// An unsliced sketch product (more than 128 tiles) joins too when it leaves at least 32 compute
+// units idle: the plain product's tiles run there while its one long round lasts.  The paired
+// kernel always writes fp32 partial results, so the single slice goes through the summing kernel
+// like several would (same bits as the direct bf16 output: one rounding of the same fp32 value).
 bool pair_ok(int cfg_a, int depth_a, const SketchPlan &p) {
-    if (p.cfg == SK_NARROW || p.splits < 2) return false;
+    if (p.cfg == SK_NARROW) return false;
+    if (p.splits < 2 && !(p.tiles > 128 && p.tiles <= 224)) return false;
     return cfg_a == GEMM_LARGE || (cfg_a == GEMM_SPLIT && depth_a == 4);
 }
 
@@ -231,7 +236,7 @@ SketchPlan plan_pass_sketch(int64_t n, int64_t d_sk, int64_t d_other, int64_t k)
         const SketchPlan finer = plan_sketch(n, d_sk, k, 320);
         if (finer.splits > paired.splits && finer.k_chunk <= 1024) paired = finer;
     }
-    return paired.splits >= 2 ? paired : alone;
+    return paired.splits >= 2 || pair_ok(cfg_a, depth_a, paired) ? paired : alone;
 }
 
 }  // namespace
@@ -315,8 +320,17 @@ hipError_t launch_xty_sumsq_bf16(const bf16_t *X, const bf16_t *dY, double *part
 
 size_t sketch_workspace_bf16(int64_t n, int64_t d, int64_t k, int64_t d_other) {
     int64_t k_chunk;
-    const int s = k <= kSmallK ? smallk_slices(n, d, k, &k_chunk)
-                               : (d_other > 0 ? plan_pass_sketch(n, d, d_other, k) : plan_sketch(n, d, k)).splits;
+    if (k <= kSmallK) {
+        const int s = smallk_slices(n, d, k, &k_chunk);
+        return s > 1 ? (size_t)s * (size_t)k * (size_t)d * sizeof(float) : 0;
+    }
+    if (d_other > 0) {  // inside a pass: a paired launch writes partial results even for a single slice
+        const SketchPlan p = plan_pass_sketch(n, d, d_other, k);
+        const int cfg_a = gemm_cfg(n, d_other, d);
+        const bool paired = pair_ok(cfg_a, cfg_a == GEMM_SPLIT ? plain_depth(d, ShapeSplit::BK) : 3, p);
+        return p.splits > 1 || paired ? (size_t)p.splits * (size_t)k * (size_t)d * sizeof(float) : 0;
+    }
+    const int s = plan_sketch(n, d, k).splits;
     return s > 1 ? (size_t)s * (size_t)k * (size_t)d * sizeof(float) : 0;
 }
 
@@ -360,7 +374,7 @@ hipError_t launch_forward_pair_bf16(const bf16_t *X, const bf16_t *W, const bf16
                                     hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end) {
     const GemmArgs ga = args_nt(X, W, bias, Y, n, d_in, d_out);
     const SketchPlan p = plan_pass_sketch(n, d_in, d_out, k);
-    const GemmArgs gb = args_sketch(X, n, d_in, k, st, p, X_proj, ws);
+    const GemmArgs gb = args_sketch(X, n, d_in, k, st, p, X_proj, ws, true);
     EventPair pev(ev_begin, ev_end, stream);
     hipError_t e;
     if (gemm_cfg(ga.M, ga.N, ga.K) == GEMM_LARGE)
@@ -403,7 +417,7 @@ hipError_t launch_backward_pair_bf16(const bf16_t *dY, const bf16_t *W, bf16_t *
                                      hipEvent_t ev_begin, hipEvent_t ev_end, bf16_t *dbias, bool accumulate_dbias) {
     const GemmArgs ga = args_nn(dY, W, dX, n, d_in, d_out);
     const SketchPlan p = plan_pass_sketch(n, d_out, d_in, k);
-    const GemmArgs gb = args_sketch(dY, n, d_out, k, st, p, G, ws);
+    const GemmArgs gb = args_sketch(dY, n, d_out, k, st, p, G, ws, true);
     const ColsumArgs gc{dY, dbias, n, d_out, accumulate_dbias ? 1 : 0, colsum_lpr(d_out, 2)};
     const ColsumArgs *gcp = dbias != nullptr ? &gc : nullptr;
     EventPair pev(ev_begin, ev_end, stream);

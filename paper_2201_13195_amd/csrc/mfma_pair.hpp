@@ -18,6 +18,7 @@ enum { SK_NARROW = 0, SK_WIDE = 1, SK_WIDE64 = 2, SK_MID64 = 3, SK_MID = 4 };
 //   nn_split: dX = dY W, 128 x 128 x 64 tiles with two wave groups (GEMM_SPLIT, depth 4)
 // sk_cfg is one of SK_WIDE, SK_WIDE64, SK_MID64, SK_MID; anything else returns hipErrorInvalidValue.
 // `gc`, if not null, adds the column blocks of a column-sum problem (colsum.hpp) behind the sketch work-groups.
+// An unsliced sketch product (splits == 1: few, long work-groups) is put in front of the plain tiles.
 hipError_t launch_pair_nt(int sk_cfg, int kind, const GemmArgs &ga, const GemmArgs &gb, int blocks_a, int tiles_b,
                           int splits, hipStream_t stream, const ColsumArgs *gc = nullptr);
 hipError_t launch_pair_nt_split(int sk_cfg, int kind, const GemmArgs &ga, const GemmArgs &gb, int blocks_a, int tiles_b,
@@ -46,11 +47,11 @@ hipError_t launch_pair_impl(int sk_cfg, int kind, const GemmArgs &ga, const Gemm
 #define RMM_PAIR_CASE(CFG, SHAPE)                                                                                      \
     case CFG * 2:                                                                                                      \
         gemm_pair_kernel<SA, A_KCONTIG, BMODE_A, DA, SHAPE, A_GAUSS_LDS, 3>                                           \
-            <<<grid, SA::THREADS, 0, stream>>>(ga, gb, blocks_a, tiles_b, sketch_blocks, c);                                             \
+            <<<grid, SA::THREADS, 0, stream>>>(ga, gb, blocks_a, tiles_b, sketch_blocks, splits == 1 ? 1 : 0, c);                                             \
         break;                                                                                                         \
     case CFG * 2 + 1:                                                                                                  \
         gemm_pair_kernel<SA, A_KCONTIG, BMODE_A, DA, SHAPE, A_RADEM_LDS, 3>                                           \
-            <<<grid, SA::THREADS, 0, stream>>>(ga, gb, blocks_a, tiles_b, sketch_blocks, c);                                             \
+            <<<grid, SA::THREADS, 0, stream>>>(ga, gb, blocks_a, tiles_b, sketch_blocks, splits == 1 ? 1 : 0, c);                                             \
         break;
     switch (key) {
         RMM_PAIR_CASE(SK_WIDE, ShapeSkWide)

@@ -340,13 +340,16 @@ def test_bias_gradient_at_paper_sizes(dtype, n, d_out):
 
 
 @pytest.mark.parametrize("kind", [rmm.GAUSSIAN, rmm.RADEMACHER])
-@pytest.mark.parametrize("name", ["c2_base_attn", "c3_base_ffn_up", "c3_base_ffn_down", "c4_large_ffn_up"])
-def test_paired_launch_gives_the_bits_of_the_separate_launches(name, kind):
+@pytest.mark.parametrize("name,k_override", [("c2_base_attn", 0), ("c3_base_ffn_up", 0), ("c3_base_ffn_down", 0),
+                                             ("c4_large_ffn_up", 0), ("c3_base_ffn_up", 3686), ("c3_base_ffn_down", 3686)])
+def test_paired_launch_gives_the_bits_of_the_separate_launches(name, k_override, kind):
     """At these shapes a pass runs its plain product and its sketch product as one launch; asking
     for a single product's stage makes it launch them one after the other, with the same token
-    slices.  Same tiles, same order of additions: every output must agree bit for bit."""
+    slices.  Same tiles, same order of additions: every output must agree bit for bit.  At
+    k = 3686 the sketch product of the 3072-wide operand is unsliced: alone it writes bf16
+    directly, in the paired launch it goes through a single fp32 slice."""
     c = synth.CONFIGS[name]
-    n, d_in, d_out, k = c["n"], c["d_in"], c["d_out"], c["k"]
+    n, d_in, d_out, k = c["n"], c["d_in"], c["d_out"], k_override or c["k"]
     assert rmm.rmm_uses_paired_launch(n, d_in, d_out, k, torch.bfloat16, kind, binding.OP_FORWARD)
     assert rmm.rmm_uses_paired_launch(n, d_in, d_out, k, torch.bfloat16, kind, binding.OP_BACKWARD)
     X, W, dY = synth.layer_inputs(n, d_in, d_out, "bf16", c["seeds"])
