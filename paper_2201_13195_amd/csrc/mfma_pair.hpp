@@ -18,7 +18,9 @@ enum { SK_NARROW = 0, SK_WIDE = 1, SK_WIDE64 = 2, SK_MID64 = 3, SK_MID = 4 };
 //   nn_split: dX = dY W, 128 x 128 x 64 tiles with two wave groups (GEMM_SPLIT, depth 4)
 // sk_cfg is one of SK_WIDE, SK_WIDE64, SK_MID64, SK_MID; anything else returns hipErrorInvalidValue.
 // `gc`, if not null, adds the column blocks of a column-sum problem (colsum.hpp) behind the sketch work-groups.
-// An unsliced sketch product (splits == 1: few, long work-groups) is put in front of the plain tiles.
+// The sketch work-groups are put in front of the plain tiles when the sketch product is unsliced (few, long
+// work-groups) or the plain product fills the chip at least once (256 tiles or more: measured 4 % faster at the
+// RoBERTa-large shapes, 2-3 % slower where the plain product has 192 tiles and the sketch work-groups fill in behind).
 hipError_t launch_pair_nt(int sk_cfg, int kind, const GemmArgs &ga, const GemmArgs &gb, int blocks_a, int tiles_b,
                           int splits, hipStream_t stream, const ColsumArgs *gc = nullptr);
 hipError_t launch_pair_nt_split(int sk_cfg, int kind, const GemmArgs &ga, const GemmArgs &gb, int blocks_a, int tiles_b,
@@ -41,17 +43,18 @@ template <typename SA, int BMODE_A, int DA>
 hipError_t launch_pair_impl(int sk_cfg, int kind, const GemmArgs &ga, const GemmArgs &gb, int blocks_a, int tiles_b,
                             int splits, hipStream_t stream, const ColsumArgs *gc) {
     const int sketch_blocks = tiles_b * splits;
+    const int sketch_first = splits == 1 || blocks_a >= 256 ? 1 : 0;
     const ColsumArgs c = gc != nullptr ? *gc : ColsumArgs{};
     const dim3 grid((unsigned)(blocks_a + sketch_blocks + (gc != nullptr ? colsum_blocks(c.d, 2) : 0)));
     const int key = sk_cfg * 2 + (kind != 0 ? 1 : 0);
 #define RMM_PAIR_CASE(CFG, SHAPE)                                                                                      \
     case CFG * 2:                                                                                                      \
         gemm_pair_kernel<SA, A_KCONTIG, BMODE_A, DA, SHAPE, A_GAUSS_LDS, 3>                                           \
-            <<<grid, SA::THREADS, 0, stream>>>(ga, gb, blocks_a, tiles_b, sketch_blocks, splits == 1 ? 1 : 0, c);                                             \
+            <<<grid, SA::THREADS, 0, stream>>>(ga, gb, blocks_a, tiles_b, sketch_blocks, sketch_first, c);             \
         break;                                                                                                         \
     case CFG * 2 + 1:                                                                                                  \
         gemm_pair_kernel<SA, A_KCONTIG, BMODE_A, DA, SHAPE, A_RADEM_LDS, 3>                                           \
-            <<<grid, SA::THREADS, 0, stream>>>(ga, gb, blocks_a, tiles_b, sketch_blocks, splits == 1 ? 1 : 0, c);                                             \
+            <<<grid, SA::THREADS, 0, stream>>>(ga, gb, blocks_a, tiles_b, sketch_blocks, sketch_first, c);             \
         break;
     switch (key) {
         RMM_PAIR_CASE(SK_WIDE, ShapeSkWide)
