@@ -45,16 +45,17 @@ hipError_t launch_pair_impl(int sk_cfg, int kind, const GemmArgs &ga, const Gemm
     const int sketch_blocks = tiles_b * splits;
     const int sketch_first = splits == 1 || blocks_a >= 256 ? 1 : 0;
     const ColsumArgs c = gc != nullptr ? *gc : ColsumArgs{};
-    const dim3 grid((unsigned)(blocks_a + sketch_blocks + (gc != nullptr ? colsum_blocks(c.d, 2) : 0)));
+    const int col_blocks = gc != nullptr ? (int)colsum_blocks(c.d, 2) : 0;
+    const dim3 grid((unsigned)(blocks_a + sketch_blocks + col_blocks));
     const int key = sk_cfg * 2 + (kind != 0 ? 1 : 0);
 #define RMM_PAIR_CASE(CFG, SHAPE)                                                                                      \
     case CFG * 2:                                                                                                      \
         gemm_pair_kernel<SA, A_KCONTIG, BMODE_A, DA, SHAPE, A_GAUSS_LDS, 3>                                           \
-            <<<grid, SA::THREADS, 0, stream>>>(ga, gb, blocks_a, tiles_b, sketch_blocks, sketch_first, c);             \
+            <<<grid, SA::THREADS, 0, stream>>>(ga, gb, blocks_a, tiles_b, sketch_blocks, col_blocks, sketch_first, c); \
         break;                                                                                                         \
     case CFG * 2 + 1:                                                                                                  \
         gemm_pair_kernel<SA, A_KCONTIG, BMODE_A, DA, SHAPE, A_RADEM_LDS, 3>                                           \
-            <<<grid, SA::THREADS, 0, stream>>>(ga, gb, blocks_a, tiles_b, sketch_blocks, sketch_first, c);             \
+            <<<grid, SA::THREADS, 0, stream>>>(ga, gb, blocks_a, tiles_b, sketch_blocks, col_blocks, sketch_first, c); \
         break;
     switch (key) {
         RMM_PAIR_CASE(SK_WIDE, ShapeSkWide)
