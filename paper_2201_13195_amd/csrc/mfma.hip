@@ -275,7 +275,7 @@ template <typename S>
 static hipError_t launch_dw_colsum(const GemmArgs &g, const ColsumArgs &c, hipStream_t stream) {
     const int blocks_a = (int)tiles_of(g.M, g.N, S::BM, S::BN);
     const dim3 grid((unsigned)(blocks_a + colsum_blocks(c.d, 2)));
-    if (std::is_same<S, ShapeLarge>::value || plain_depth(g.K, S::BK) == 3)
+    if (plain_depth(g.K, S::BK) == 3)
         dw_colsum_kernel<S, 3><<<grid, S::THREADS, 0, stream>>>(g, c, blocks_a);
     else
         dw_colsum_kernel<S, 4><<<grid, S::THREADS, 0, stream>>>(g, c, blocks_a);
@@ -290,7 +290,10 @@ hipError_t launch_dw_colsum_bf16(const bf16_t *G, const bf16_t *X_proj, bf16_t *
     g.M = d_out, g.N = d_in, g.K = k, g.alpha = 1.0f, g.k_chunk = (k + 127) / 128 * 128;
     const ColsumArgs c{dY, dbias, n, d_out, accumulate ? 1 : 0, colsum_lpr(d_out, 2)};
     switch (gemm_cfg(g.M, g.N, g.K)) {  // the tile dW runs with on its own
-        case GEMM_LARGE: return launch_dw_colsum<ShapeLarge>(g, c, stream);
+        case GEMM_LARGE: {  // 160 or more tiles of 256 x 256: dW fills the chip, the column sums follow as a launch of their own
+            const hipError_t e = launch_dw_bf16(G, X_proj, dW, k, d_in, d_out, stream, accumulate);
+            return e != hipSuccess ? e : launch_colsum<bf16_t>(dY, dbias, n, d_out, stream, accumulate);
+        }
         case GEMM_SPLIT: return launch_dw_colsum<ShapeSplit>(g, c, stream);
         case GEMM_TINY: return launch_dw_colsum<ShapeTiny>(g, c, stream);
         default: return launch_dw_colsum<ShapeMid>(g, c, stream);
