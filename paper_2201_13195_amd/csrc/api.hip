@@ -237,7 +237,7 @@ int backward_impl(const rmm_layer_desc_t *d, SketchState st, const void *dY, con
 
 extern "C" {
 
-int rmm_version(void) { return 312; }
+int rmm_version(void) { return 313; }
 
 const char *rmm_status_string(int status) {
     switch (status) {
